@@ -1,0 +1,282 @@
+#!/usr/bin/env python3
+"""Benchmark of the superposition-prompting hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic input shaped like
+the 7B-class multi-head workload (8 prompts x 20 document paths, 64-token preamble, 128-token
+documents, 24-token query copies, vocabulary 50432):
+
+    sp_forkjoin_prefill -> sp_path_saliency -> sp_prune_topk -> 5 x sp_pruned_decode
+
+(5 decode steps: the paper's timing protocol generates a 5-token response, App. C).  Inputs
+are resident in HBM before the timed region; two input sets are rotated so that no step finds
+its inputs in the 256 MB last-level cache.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-decode-c5]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import sp_synth  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+
+
+def kv_bytes_per_token(n_kv_heads: int, head_dim: int, elem_bytes: int) -> int:
+    """K and V bytes of one token in one layer (the per-layer factor of the paper's cache
+    memory model, Sec. 3.3.1)."""
+    return 2 * n_kv_heads * head_dim * elem_bytes
+
+
+def prefill_flops(pairs: int, n_q_heads: int, head_dim: int) -> int:
+    """2*d for q.k plus 2*d for p.v per visible (query, key) pair and head."""
+    return 4 * head_dim * n_q_heads * pairs
+
+
+def prefill_bytes(n_tokens: int, n_q_heads: int, n_kv_heads: int, head_dim: int, esz: int) -> int:
+    """Compulsory traffic: read Q, K, V once, write O once."""
+    return n_tokens * head_dim * esz * (2 * n_q_heads + 2 * n_kv_heads)
+
+
+def decode_step_bytes(n_keys_total: int, n_kv_heads: int, head_dim: int, esz: int) -> int:
+    """K and V rows streamed by one decode step (n_keys_total summed over prompts)."""
+    return n_keys_total * kv_bytes_per_token(n_kv_heads, head_dim, esz)
+
+
+def _device_inputs(wl, seed, torch):
+    """One input set of the workload, generated on the device from a seeded generator."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    st = sp_synth.forkjoin_segtable(wl.preamble_len, sp_synth.draw_doc_lens(wl, np.random.default_rng(seed)),
+                                    wl.query_len)
+    T = st.n_tokens
+    rn = lambda *s: torch.randn(s, generator=g, device="cuda", dtype=torch.float32)
+    d = {"st": st}
+    d["Q"] = rn(T, wl.n_q_heads, wl.head_dim).to(torch.bfloat16)
+    d["K"] = rn(T, wl.n_kv_heads, wl.head_dim).to(torch.bfloat16)
+    d["V"] = rn(T, wl.n_kv_heads, wl.head_dim).to(torch.bfloat16)
+    d["O"] = torch.empty_like(d["Q"])
+    R = st.n_slots * wl.query_len
+    logits = torch.empty((R, wl.vocab), dtype=torch.bfloat16, device="cuda")
+    for r in range(0, R, 512):
+        n = min(512, R - r)
+        logits[r:r + n] = rn(n, wl.vocab) * wl.logit_std
+    d["logits"] = logits
+    rng = np.random.default_rng(seed + 1)
+    tgt = np.concatenate([np.tile(rng.integers(0, wl.vocab, size=wl.query_len), wl.n_paths)
+                          for _ in range(wl.n_prompts)]).astype(np.int32)
+    d["target"] = torch.from_numpy(tgt).cuda()
+    d["row_path"] = torch.from_numpy(np.repeat(np.arange(st.n_slots), wl.query_len).astype(np.int32)).cuda()
+    d["score"] = torch.empty(st.n_slots, device="cuda")
+    d["kept"] = torch.empty((wl.n_prompts, wl.top_k), dtype=torch.int32, device="cuda")
+    S = wl.decode_steps
+    d["dq"] = rn(S, wl.n_prompts, wl.n_q_heads, wl.head_dim).to(torch.bfloat16)
+    d["dk"] = rn(S, wl.n_prompts, wl.n_kv_heads, wl.head_dim).to(torch.bfloat16)
+    d["dv"] = rn(S, wl.n_prompts, wl.n_kv_heads, wl.head_dim).to(torch.bfloat16)
+    d["Kr"] = torch.zeros((wl.n_prompts, S, wl.n_kv_heads, wl.head_dim), dtype=torch.bfloat16, device="cuda")
+    d["Vr"] = torch.zeros_like(d["Kr"])
+    d["o"] = torch.empty((wl.n_prompts, wl.n_q_heads, wl.head_dim), dtype=torch.bfloat16, device="cuda")
+    return d
+
+
+def _cpu_baseline(wl, budget_s=12.0):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: complete
+    prefill attention of successive (prompt 0, head h) pairs until the time budget is used."""
+    from oracle import sp_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    inp = sp_synth.make_inputs(wl, n_prompts=1, with_logits=False, with_decode=False)
+    st = inp.st
+    seg = st.n_segments
+    # pairs per head of one prompt
+    anc = 0
+    P = wl.preamble_len
+    pairs = P * (P + 1) // 2
+    for s in range(st.n_slots):
+        L = int(st.seg_tok_len[st.doc_seg[s]] + st.seg_tok_len[st.query_seg[s]])
+        pairs += L * P + L * (L + 1) // 2
+    scale = 1 / math.sqrt(wl.head_dim)
+    t0 = time.perf_counter()
+    n = 0
+    while n < wl.n_q_heads:
+        orc.forkjoin_prefill(inp.q, inp.k, inp.v, st.prompt_seg_off, st.seg_tok_start, st.seg_tok_len, st.seg_parent,
+                             scale, prompts=[0], heads=[n])
+        n += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    flops = prefill_flops(pairs, 1, wl.head_dim) * n
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": "prefill attention of %d (prompt, head) pairs of %s (1 prompt of %d tokens each; dense fp64 "
+                      "T x T oracle; rate = algorithmic FLOPs / wall time), %.1f s" % (n, wl.name, st.n_tokens, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2_mha7b_bf16")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode-c5", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU by design (one process, one MI355X); --gpus %d is not "
+              "supported: no collectives or sharding exist in this library" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2404_06910_amd import binding as B
+
+    wl = sp_synth.WORKLOADS[args.workload]
+    assert wl.dtype == "bf16"
+    torch.cuda.set_device(0)
+    ctx = B.Context(0)                       # launches on torch's current stream
+    sets = [_device_inputs(wl, wl.seed + 17 * i, torch) for i in range(2)]
+    st = sets[0]["st"]
+    plans = []
+    t_plan = time.perf_counter()
+    for s in sets:
+        t = s["st"]
+        plans.append(B.Plan(ctx, t.prompt_seg_off, t.seg_tok_start, t.seg_tok_len, t.seg_parent, t.seg_path,
+                            t.n_tokens, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, B.SP_BF16))
+    t_plan = (time.perf_counter() - t_plan) / len(sets)
+    scale = 1 / math.sqrt(wl.head_dim)
+    S = wl.decode_steps
+    path_off_dev = [p.path_offsets_device() for p in plans]
+
+    def step(i, ev=None):
+        d, plan = sets[i % 2], plans[i % 2]
+        if ev: ev[0].record()
+        ctx.sp_forkjoin_prefill(plan, d["Q"], d["K"], d["V"], d["O"], scale)
+        if ev: ev[1].record()
+        ctx.sp_path_saliency(d["logits"], d["target"], d["row_path"], d["st"].n_slots, d["score"])
+        if ev: ev[2].record()
+        ctx.sp_prune_topk(d["score"], path_off_dev[i % 2], wl.n_prompts, wl.n_paths, wl.top_k, d["kept"])
+        if ev: ev[3].record()
+        for s in range(S):
+            ctx.sp_pruned_decode(plan, d["kept"], wl.top_k, d["K"], d["V"], d["Kr"], d["Vr"], S, d["dq"][s],
+                                 d["dk"][s], d["dv"][s], d["o"], scale, resp_len_add=s)
+        if ev: ev[4].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ph = np.array([[ev[j].elapsed_time(ev[j + 1]) for j in range(4)] for ev in events])   # ms
+    med = np.median(ph, axis=0)
+    mean = ph.mean(axis=0)
+
+    pairs = plans[0].visible_pairs()
+    flops = prefill_flops(pairs, wl.n_q_heads, wl.head_dim)
+    pbytes = prefill_bytes(st.n_tokens, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, 2)
+    t_pre = mean[0] * 1e-3
+    tflops = flops / t_pre / 1e12
+    sal_bytes = sets[0]["logits"].numel() * 2
+    sal_gbs = sal_bytes / (mean[1] * 1e-3) / 1e9
+    kept_keys = wl.preamble_len + wl.top_k * (int(st.seg_tok_len[st.doc_seg[0]]) + wl.query_len)
+    dec_bytes = sum(decode_step_bytes(wl.n_prompts * (kept_keys + s + 1), wl.n_kv_heads, wl.head_dim, 2) for s in range(S))
+    dec_gbs = dec_bytes / (mean[3] * 1e-3) / 1e9
+
+    out = {
+        "metric": "forkjoin_prefill_tflops", "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall / args.steps * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "n_prompts": wl.n_prompts, "n_paths": wl.n_paths, "n_q_heads": wl.n_q_heads,
+                   "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "preamble": wl.preamble_len,
+                   "doc_len": wl.doc_len, "query_len": wl.query_len, "vocab": wl.vocab, "top_k": wl.top_k,
+                   "decode_steps": S, "tokens": st.n_tokens, "input_sets_rotated": 2},
+        "phase_ms_mean": {"prefill": round(mean[0], 4), "saliency": round(mean[1], 4), "topk": round(mean[2], 4),
+                          "decode_%d_steps" % S: round(mean[3], 4)},
+        "phase_ms_median": {"prefill": round(med[0], 4), "saliency": round(med[1], 4), "topk": round(med[2], 4),
+                            "decode_%d_steps" % S: round(med[3], 4)},
+        "plan_create_ms": round(t_plan * 1e3, 3),
+        # dominant kernel: prefill.  Its arithmetic intensity at this shape (flops/compulsory bytes) is
+        # below the machine balance, so HBM is the binding roof; the MFMA view is given next to it.
+        "roofline": {"kernel": "prefill_bf16_kernel", "bound": "hbm", "achieved": round(pbytes / t_pre / 1e9, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(pbytes / t_pre / 1e9 / HBM_PEAK_GBS, 4),
+                     "traffic": None, "algorithmic_bytes": pbytes, "algorithmic_flops": flops,
+                     "intensity_flop_per_byte": round(flops / pbytes, 1), "avg_launch_ms": round(mean[0], 4)},
+        "roofline_mfma": {"kernel": "prefill_bf16_kernel", "bound": "mfma", "achieved": round(tflops, 2),
+                          "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                          "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+                          "hbm_ceiling_frac": round(flops / pbytes * HBM_PEAK_GBS * 1e9 / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)},
+        "saliency": {"kernel": "row_loglik_kernel", "bound": "hbm", "achieved": round(sal_gbs, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(sal_gbs / HBM_PEAK_GBS, 4), "algorithmic_bytes": sal_bytes},
+        "decode_in_step": {"kernel": "decode_kernel", "bound": "hbm", "achieved": round(dec_gbs, 1),
+                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dec_gbs / HBM_PEAK_GBS, 4),
+                           "algorithmic_bytes": dec_bytes, "note": "8 prompts only: launch-latency bound"},
+    }
+    tr = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tr):
+        try:
+            out["roofline"]["traffic"] = json.load(open(tr)).get("prefill_bf16_kernel:" + wl.name)
+        except Exception:
+            pass
+
+    if not args.no_decode_c5:
+        out["decode_c5"] = _bench_decode_c5(ctx, torch, B)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = _cpu_baseline(wl)
+    print(json.dumps(out))
+
+
+def _bench_decode_c5(ctx, torch, B):
+    """Long pruned decode: 64 prompts, 2 of 20 paths kept, 256 steps over the growing cache."""
+    wl = sp_synth.WORKLOADS["c5_decode_bf16"]
+    st = sp_synth.forkjoin_segtable(wl.preamble_len, [[wl.doc_len] * wl.n_paths] * wl.n_prompts, wl.query_len)
+    g = torch.Generator(device="cuda"); g.manual_seed(wl.seed)
+    H, d, S, Bn = wl.n_kv_heads, wl.head_dim, wl.decode_steps, wl.n_prompts
+    rn = lambda *s: torch.randn(s, generator=g, device="cuda").to(torch.bfloat16)
+    K, V = rn(st.n_tokens, H, d), rn(st.n_tokens, H, d)
+    dq, dk, dv = rn(S, Bn, H, d), rn(S, Bn, H, d), rn(S, Bn, H, d)
+    rng = np.random.default_rng(wl.seed)
+    kept = torch.from_numpy(np.stack([rng.permutation(wl.n_paths)[:wl.top_k] for _ in range(Bn)]).astype(np.int32)).cuda()
+    plan = B.Plan(ctx, st.prompt_seg_off, st.seg_tok_start, st.seg_tok_len, st.seg_parent, st.seg_path, st.n_tokens,
+                  H, H, d, B.SP_BF16)
+    Kr = torch.zeros((Bn, S, H, d), dtype=torch.bfloat16, device="cuda"); Vr = torch.zeros_like(Kr)
+    o = torch.empty((S, Bn, H, d), dtype=torch.bfloat16, device="cuda")
+    scale = 1 / math.sqrt(d)
+
+    def loop():
+        for s in range(S):
+            ctx.sp_pruned_decode(plan, kept, wl.top_k, K, V, Kr, Vr, S, dq[s], dk[s], dv[s], o[s], scale, resp_len_add=s)
+
+    loop()
+    torch.cuda.synchronize()
+    times = []
+    for _ in range(5):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); loop(); e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1))
+    ms = float(np.median(times))
+    kept_keys = wl.preamble_len + wl.top_k * (wl.doc_len + wl.query_len)
+    total = sum(decode_step_bytes(Bn * (kept_keys + s + 1), H, d, 2) for s in range(S))
+    gbs = total / (ms * 1e-3) / 1e9
+    return {"workload": wl.name, "kernel": "decode_kernel", "bound": "hbm", "achieved": round(gbs, 1),
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "algorithmic_bytes": total,
+            "loop_ms_median": round(ms, 3), "us_per_step": round(ms * 1e3 / S, 2), "steps": S}
+
+
+if __name__ == "__main__":
+    main()

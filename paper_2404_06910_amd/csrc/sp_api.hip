@@ -1,0 +1,568 @@
+// Host side of libsp.so: contexts, plan construction (validation, ancestor chains, tile work
+// list, decode gather tables), argument checks and kernel dispatch.  No kernels live here.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <numeric>
+
+#include "sp_internal.h"
+
+namespace {
+
+thread_local std::string g_err;   // failures of calls that have no context
+
+sp_status fail(std::string *dst, sp_status st, const char *fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  (dst ? *dst : g_err) = buf;
+  return st;
+}
+
+std::string *errslot(sp_ctx *ctx) { return ctx ? &ctx->err : nullptr; }
+
+#define SP_HIP(ctx, call)                                                                     \
+  do {                                                                                        \
+    hipError_t e_ = (call);                                                                   \
+    if (e_ != hipSuccess)                                                                     \
+      return fail(errslot(ctx), SP_ERR_HIP, "%s failed: %s", #call, hipGetErrorString(e_));   \
+  } while (0)
+
+// ---------------------------------------------------------------------------------------
+// Table validation (Sec. 3.2: the prompt DAG; here a forest with one parent per node)
+// ---------------------------------------------------------------------------------------
+sp_status validate_table(const sp_segtable *t, int32_t n_q_heads, std::string *err) {
+  if (!t) return fail(err, SP_ERR_INVALID_ARG, "segment table is NULL");
+  if (t->n_prompts <= 0 || t->n_segments <= 0 || t->n_tokens <= 0)
+    return fail(err, SP_ERR_INVALID_ARG, "n_prompts, n_segments and n_tokens must be positive");
+  if (!t->prompt_seg_off || !t->seg_tok_start || !t->seg_tok_len || !t->seg_parent || !t->seg_path)
+    return fail(err, SP_ERR_INVALID_ARG, "segment table has a NULL array");
+  if (t->alibi_slopes && !t->tok_pos)
+    return fail(err, SP_ERR_INVALID_ARG, "alibi_slopes given without tok_pos");
+  const int32_t B = t->n_prompts, S = t->n_segments, T = t->n_tokens;
+  if (t->prompt_seg_off[0] != 0 || t->prompt_seg_off[B] != S)
+    return fail(err, SP_ERR_BAD_TABLE, "prompt_seg_off must start at 0 and end at n_segments");
+  for (int32_t b = 0; b < B; ++b)
+    if (t->prompt_seg_off[b + 1] <= t->prompt_seg_off[b])
+      return fail(err, SP_ERR_BAD_TABLE, "prompt %d has no segments (prompt_seg_off not increasing)", b);
+  std::vector<std::pair<int64_t, int64_t>> spans(S);
+  for (int32_t s = 0; s < S; ++s) {
+    const int64_t a = t->seg_tok_start[s], n = t->seg_tok_len[s];
+    if (n <= 0) return fail(err, SP_ERR_BAD_TABLE, "segment %d has non-positive length", s);
+    if (a < 0 || a + n > T) return fail(err, SP_ERR_BAD_TABLE, "segment %d token range out of [0, n_tokens)", s);
+    spans[s] = {a, a + n};
+  }
+  std::sort(spans.begin(), spans.end());
+  for (int32_t s = 1; s < S; ++s)
+    if (spans[s].first < spans[s - 1].second)
+      return fail(err, SP_ERR_BAD_TABLE, "token ranges of two segments overlap near token %lld",
+                  (long long)spans[s].first);
+  for (int32_t b = 0; b < B; ++b) {
+    const int32_t s0 = t->prompt_seg_off[b], s1 = t->prompt_seg_off[b + 1];
+    int32_t max_path = -1;
+    for (int32_t s = s0; s < s1; ++s) {
+      const int32_t p = t->seg_parent[s], path = t->seg_path[s];
+      if (p != -1 && (p < s0 || p >= s))
+        return fail(err, SP_ERR_BAD_TABLE, "segment %d: parent %d is not an earlier segment of the same prompt", s, p);
+      if (path < -1) return fail(err, SP_ERR_BAD_TABLE, "segment %d: path id below -1", s);
+      if (p != -1) {
+        const int32_t ppath = t->seg_path[p];
+        if (path == -1 && ppath != -1)
+          return fail(err, SP_ERR_BAD_TABLE, "segment %d is shared but its parent lies on path %d", s, ppath);
+        if (path >= 0 && ppath != -1 && ppath != path)
+          return fail(err, SP_ERR_BAD_TABLE, "segment %d on path %d has a parent on path %d", s, path, ppath);
+      }
+      max_path = std::max(max_path, path);
+    }
+    std::vector<char> used(max_path + 1, 0);
+    for (int32_t s = s0; s < s1; ++s)
+      if (t->seg_path[s] >= 0) used[t->seg_path[s]] = 1;
+    for (int32_t p = 0; p <= max_path; ++p)
+      if (!used[p]) return fail(err, SP_ERR_BAD_TABLE, "prompt %d: path ids are not dense (path %d unused)", b, p);
+  }
+  if (t->tok_pos)
+    for (int32_t i = 0; i < T; ++i)
+      if (!std::isfinite(t->tok_pos[i])) return fail(err, SP_ERR_BAD_TABLE, "tok_pos[%d] is not finite", i);
+  if (t->alibi_slopes)
+    for (int32_t h = 0; h < n_q_heads; ++h)
+      if (!std::isfinite(t->alibi_slopes[h]) || t->alibi_slopes[h] < 0.f)
+        return fail(err, SP_ERR_BAD_TABLE, "alibi_slopes[%d] must be finite and >= 0", h);
+  return SP_OK;
+}
+
+void push_range(std::vector<sp::KeyRange> &v, size_t first, int32_t start, int32_t len) {
+  if (v.size() > first && v.back().tok_start + v.back().len == start)
+    v.back().len += len;            // merge neighbours in token space
+  else
+    v.push_back({start, len});
+}
+
+template <class T>
+size_t blob_reserve(size_t &off, const std::vector<T> &v) {
+  off = (off + 255) & ~size_t(255);
+  const size_t at = off;
+  off += v.size() * sizeof(T) + 16;
+  return at;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------
+// Context
+// ---------------------------------------------------------------------------------------
+extern "C" const char *sp_version(void) { return "sp-forkjoin 0.1 (gfx950)"; }
+
+extern "C" const char *sp_last_error(const sp_ctx *ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
+
+extern "C" sp_status sp_create(sp_ctx **out, int device, void *hip_stream) {
+  if (!out) return fail(nullptr, SP_ERR_INVALID_ARG, "out is NULL");
+  *out = nullptr;
+  int n = 0;
+  hipError_t e = hipGetDeviceCount(&n);
+  if (e != hipSuccess || n <= 0)
+    return fail(nullptr, SP_ERR_HIP, "no usable HIP device (%s)", e == hipSuccess ? "count is 0" : hipGetErrorString(e));
+  if (device < 0 || device >= n) return fail(nullptr, SP_ERR_INVALID_ARG, "device %d out of range [0,%d)", device, n);
+  SP_HIP(nullptr, hipSetDevice(device));
+  sp_ctx *c = new (std::nothrow) sp_ctx;
+  if (!c) return fail(nullptr, SP_ERR_WORKSPACE, "out of host memory");
+  c->device = device;
+  c->stream = static_cast<hipStream_t>(hip_stream);
+  *out = c;
+  return SP_OK;
+}
+
+extern "C" void sp_destroy(sp_ctx *ctx) {
+  if (!ctx) return;
+  if (ctx->ws) (void)hipFree(ctx->ws);
+  delete ctx;
+}
+
+extern "C" sp_status sp_set_stream(sp_ctx *ctx, void *hip_stream) {
+  if (!ctx) return fail(nullptr, SP_ERR_INVALID_ARG, "ctx is NULL");
+  ctx->stream = static_cast<hipStream_t>(hip_stream);
+  return SP_OK;
+}
+
+static sp_status ensure_ws(sp_ctx *ctx, size_t bytes) {
+  if (ctx->ws_bytes >= bytes) return SP_OK;
+  if (ctx->ws) {
+    SP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    (void)hipFree(ctx->ws);
+    ctx->ws = nullptr;
+    ctx->ws_bytes = 0;
+  }
+  const size_t want = std::max(bytes, size_t(1) << 20);
+  if (hipMalloc(reinterpret_cast<void **>(&ctx->ws), want) != hipSuccess)
+    return fail(&ctx->err, SP_ERR_WORKSPACE, "could not allocate %zu bytes of workspace", want);
+  ctx->ws_bytes = want;
+  return SP_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// Plan
+// ---------------------------------------------------------------------------------------
+extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n_q_heads, int32_t n_kv_heads,
+                                    int32_t head_dim, sp_dtype dtype, sp_plan **out) {
+  std::string *err = errslot(ctx);
+  if (!out) return fail(err, SP_ERR_INVALID_ARG, "out is NULL");
+  *out = nullptr;
+  if (n_q_heads <= 0 || n_kv_heads <= 0) return fail(err, SP_ERR_INVALID_ARG, "head counts must be positive");
+  if (n_q_heads % n_kv_heads) return fail(err, SP_ERR_UNSUPPORTED, "n_q_heads must be a multiple of n_kv_heads");
+  if (head_dim != 64 && head_dim != 128) return fail(err, SP_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+  if (dtype != SP_F32 && dtype != SP_BF16) return fail(err, SP_ERR_INVALID_ARG, "unknown dtype");
+  sp_status st = validate_table(t, n_q_heads, err);
+  if (st != SP_OK) return st;
+
+  sp_plan *p = new (std::nothrow) sp_plan;
+  if (!p) return fail(err, SP_ERR_WORKSPACE, "out of host memory");
+  p->ctx = ctx;
+  p->n_prompts = t->n_prompts; p->n_segments = t->n_segments; p->n_tokens = t->n_tokens;
+  p->n_q_heads = n_q_heads; p->n_kv_heads = n_kv_heads; p->head_dim = head_dim; p->dtype = dtype;
+  const int32_t B = t->n_prompts, S = t->n_segments;
+  p->prompt_seg_off.assign(t->prompt_seg_off, t->prompt_seg_off + B + 1);
+  p->seg_tok_start.assign(t->seg_tok_start, t->seg_tok_start + S);
+  p->seg_tok_len.assign(t->seg_tok_len, t->seg_tok_len + S);
+  p->seg_parent.assign(t->seg_parent, t->seg_parent + S);
+  p->seg_path.assign(t->seg_path, t->seg_path + S);
+  p->has_pos = t->tok_pos != nullptr;
+  p->has_slopes = t->alibi_slopes != nullptr;
+
+  // --- row groups: fuse a child that is packed right behind its parent into the parent's run
+  std::vector<int32_t> group_of(S, -1), group_last;
+  std::vector<int32_t> chain;
+  for (int32_t b = 0; b < B; ++b) {
+    for (int32_t s = t->prompt_seg_off[b]; s < t->prompt_seg_off[b + 1]; ++s) {
+      const int32_t par = t->seg_parent[s];
+      if (par >= 0) {
+        const int32_t g = group_of[par];
+        if (group_last[g] == par && t->seg_tok_start[s] == t->seg_tok_start[par] + t->seg_tok_len[par]) {
+          group_of[s] = g;
+          p->groups[g].len += t->seg_tok_len[s];
+          group_last[g] = s;
+          continue;
+        }
+      }
+      sp::RowGroup rg{};
+      rg.tok_start = t->seg_tok_start[s];
+      rg.len = t->seg_tok_len[s];
+      rg.prompt = b;
+      rg.range_off = static_cast<int32_t>(p->ranges.size());
+      chain.clear();
+      for (int32_t a = par; a >= 0; a = t->seg_parent[a]) chain.push_back(a);
+      int32_t anc = 0;
+      for (auto it = chain.rbegin(); it != chain.rend(); ++it) {
+        push_range(p->ranges, rg.range_off, t->seg_tok_start[*it], t->seg_tok_len[*it]);
+        anc += t->seg_tok_len[*it];
+      }
+      rg.n_ranges = static_cast<int32_t>(p->ranges.size()) - rg.range_off;
+      rg.anc_keys = anc;
+      if (rg.n_ranges > sp::kMaxRanges) {
+        delete p;
+        return fail(err, SP_ERR_UNSUPPORTED, "segment %d has %d disjoint ancestor key ranges (limit %d)", s,
+                    rg.n_ranges, sp::kMaxRanges);
+      }
+      p->max_ranges = std::max(p->max_ranges, rg.n_ranges);
+      group_of[s] = static_cast<int32_t>(p->groups.size());
+      group_last.push_back(s);
+      p->groups.push_back(rg);
+    }
+  }
+  p->tok_group.assign(t->n_tokens, -1);
+  p->visible_pairs = 0;
+  for (size_t g = 0; g < p->groups.size(); ++g) {
+    const sp::RowGroup &rg = p->groups[g];
+    std::fill(p->tok_group.begin() + rg.tok_start, p->tok_group.begin() + rg.tok_start + rg.len,
+              static_cast<int32_t>(g));
+    p->visible_pairs += int64_t(rg.len) * rg.anc_keys + int64_t(rg.len) * (rg.len + 1) / 2;
+  }
+
+  // --- prefill work list.  Query heads that share a KV head are stacked in one workgroup
+  // (4 waves): 4, 2 or 1 heads per workgroup, each wave owning 32 token rows of one head.
+  const int32_t G = n_q_heads / n_kv_heads;
+  p->heads_per_wg = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
+  p->tile_rows = 32 * (4 / p->heads_per_wg);
+  const int32_t n_hg = n_q_heads / p->heads_per_wg;
+  {
+    size_t g = 0;
+    std::vector<std::pair<int32_t, int32_t>> tiles;   // (group, row0) of the current prompt
+    for (int32_t b = 0; b < B; ++b) {
+      tiles.clear();
+      for (; g < p->groups.size() && p->groups[g].prompt == b; ++g)
+        for (int32_t r = 0; r < p->groups[g].len; r += p->tile_rows) tiles.push_back({int32_t(g), r});
+      p->n_tiles += static_cast<int32_t>(tiles.size());
+      // Order: all tiles of one (prompt, head group) are adjacent, so workgroups that read the
+      // same K/V rows run close together in time and, after the XCD remap in the kernel, on
+      // the same L2.
+      for (int32_t hg = 0; hg < n_hg; ++hg)
+        for (auto &tl : tiles) p->items.push_back({tl.first, tl.second, hg * p->heads_per_wg, 0});
+    }
+  }
+
+  // --- decode gather tables: shared ranges per prompt, ranges per path slot
+  p->path_off.assign(B + 1, 0);
+  for (int32_t b = 0; b < B; ++b) {
+    int32_t mp = -1;
+    for (int32_t s = t->prompt_seg_off[b]; s < t->prompt_seg_off[b + 1]; ++s) mp = std::max(mp, t->seg_path[s]);
+    p->path_off[b + 1] = p->path_off[b] + mp + 1;
+  }
+  p->n_slots = p->path_off[B];
+  p->shared_rng_beg.assign(B, 0);
+  p->shared_rng_end.assign(B, 0);
+  p->path_rng_beg.assign(p->n_slots, 0);
+  p->path_rng_end.assign(p->n_slots, 0);
+  p->path_max_ranges.assign(B, 0);
+  for (int32_t b = 0; b < B; ++b) {
+    const size_t first = p->dec_ranges.size();
+    for (int32_t s = t->prompt_seg_off[b]; s < t->prompt_seg_off[b + 1]; ++s)
+      if (t->seg_path[s] < 0) push_range(p->dec_ranges, first, t->seg_tok_start[s], t->seg_tok_len[s]);
+    p->shared_rng_beg[b] = static_cast<int32_t>(first);
+    p->shared_rng_end[b] = static_cast<int32_t>(p->dec_ranges.size());
+    const int32_t np = p->path_off[b + 1] - p->path_off[b];
+    for (int32_t q = 0; q < np; ++q) {
+      const size_t pf = p->dec_ranges.size();
+      for (int32_t s = t->prompt_seg_off[b]; s < t->prompt_seg_off[b + 1]; ++s)
+        if (t->seg_path[s] == q) push_range(p->dec_ranges, pf, t->seg_tok_start[s], t->seg_tok_len[s]);
+      const int32_t slot = p->path_off[b] + q;
+      p->path_rng_beg[slot] = static_cast<int32_t>(pf);
+      p->path_rng_end[slot] = static_cast<int32_t>(p->dec_ranges.size());
+      p->path_max_ranges[b] = std::max(p->path_max_ranges[b], int32_t(p->dec_ranges.size() - pf));
+    }
+  }
+
+  // --- upload
+  if (ctx) {
+    std::vector<float> pos, slopes;
+    if (t->tok_pos) pos.assign(t->tok_pos, t->tok_pos + t->n_tokens);
+    if (t->alibi_slopes) slopes.assign(t->alibi_slopes, t->alibi_slopes + n_q_heads);
+    size_t off = 0;
+    const size_t o_groups = blob_reserve(off, p->groups), o_ranges = blob_reserve(off, p->ranges),
+                 o_items = blob_reserve(off, p->items), o_tokg = blob_reserve(off, p->tok_group),
+                 o_pos = blob_reserve(off, pos), o_slopes = blob_reserve(off, slopes),
+                 o_poff = blob_reserve(off, p->path_off), o_sb = blob_reserve(off, p->shared_rng_beg),
+                 o_se = blob_reserve(off, p->shared_rng_end), o_pb = blob_reserve(off, p->path_rng_beg),
+                 o_pe = blob_reserve(off, p->path_rng_end), o_dr = blob_reserve(off, p->dec_ranges);
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e == hipSuccess) e = hipMalloc(&p->dev_blob, off + 256);
+    if (e != hipSuccess) {
+      delete p;
+      return fail(err, SP_ERR_HIP, "plan upload: %s", hipGetErrorString(e));
+    }
+    char *base = static_cast<char *>(p->dev_blob);
+    auto up = [&](size_t at, const void *src, size_t bytes) {
+      if (bytes && e == hipSuccess) e = hipMemcpy(base + at, src, bytes, hipMemcpyHostToDevice);
+    };
+    up(o_groups, p->groups.data(), p->groups.size() * sizeof(sp::RowGroup));
+    up(o_ranges, p->ranges.data(), p->ranges.size() * sizeof(sp::KeyRange));
+    up(o_items, p->items.data(), p->items.size() * sizeof(sp::WorkItem));
+    up(o_tokg, p->tok_group.data(), p->tok_group.size() * 4);
+    up(o_pos, pos.data(), pos.size() * 4);
+    up(o_slopes, slopes.data(), slopes.size() * 4);
+    up(o_poff, p->path_off.data(), p->path_off.size() * 4);
+    up(o_sb, p->shared_rng_beg.data(), p->shared_rng_beg.size() * 4);
+    up(o_se, p->shared_rng_end.data(), p->shared_rng_end.size() * 4);
+    up(o_pb, p->path_rng_beg.data(), p->path_rng_beg.size() * 4);
+    up(o_pe, p->path_rng_end.data(), p->path_rng_end.size() * 4);
+    up(o_dr, p->dec_ranges.data(), p->dec_ranges.size() * sizeof(sp::KeyRange));
+    if (e != hipSuccess) {
+      (void)hipFree(p->dev_blob);
+      delete p;
+      return fail(err, SP_ERR_HIP, "plan upload: %s", hipGetErrorString(e));
+    }
+    sp::PlanDev &d = p->dev;
+    d.groups = reinterpret_cast<const sp::RowGroup *>(base + o_groups);
+    d.ranges = reinterpret_cast<const sp::KeyRange *>(base + o_ranges);
+    d.items = reinterpret_cast<const sp::WorkItem *>(base + o_items);
+    d.tok_group = reinterpret_cast<const int32_t *>(base + o_tokg);
+    d.tok_pos = pos.empty() ? nullptr : reinterpret_cast<const float *>(base + o_pos);
+    d.slopes = slopes.empty() ? nullptr : reinterpret_cast<const float *>(base + o_slopes);
+    d.path_off = reinterpret_cast<const int32_t *>(base + o_poff);
+    d.shared_rng_beg = reinterpret_cast<const int32_t *>(base + o_sb);
+    d.shared_rng_end = reinterpret_cast<const int32_t *>(base + o_se);
+    d.path_rng_beg = reinterpret_cast<const int32_t *>(base + o_pb);
+    d.path_rng_end = reinterpret_cast<const int32_t *>(base + o_pe);
+    d.dec_ranges = reinterpret_cast<const sp::KeyRange *>(base + o_dr);
+    d.n_items = static_cast<int32_t>(p->items.size());
+    d.n_tokens = p->n_tokens;
+    d.n_prompts = p->n_prompts;
+    d.n_q_heads = n_q_heads; d.n_kv_heads = n_kv_heads; d.head_dim = head_dim;
+  }
+  *out = p;
+  return SP_OK;
+}
+
+extern "C" void sp_plan_destroy(sp_plan *plan) {
+  if (!plan) return;
+  if (plan->dev_blob) (void)hipFree(plan->dev_blob);
+  delete plan;
+}
+
+extern "C" sp_status sp_plan_info(const sp_plan *p, int64_t info[8]) {
+  if (!p || !info) return fail(nullptr, SP_ERR_INVALID_ARG, "NULL argument");
+  info[0] = p->n_prompts; info[1] = p->n_segments; info[2] = p->n_tokens; info[3] = p->n_slots;
+  info[4] = int64_t(p->groups.size()); info[5] = p->n_tiles; info[6] = int64_t(p->items.size());
+  info[7] = p->max_ranges;
+  return SP_OK;
+}
+
+extern "C" int64_t sp_plan_visible_pairs(const sp_plan *p) { return p ? p->visible_pairs : SP_ERR_INVALID_ARG; }
+
+extern "C" sp_status sp_plan_path_offsets(const sp_plan *p, int32_t *out) {
+  if (!p || !out) return fail(nullptr, SP_ERR_INVALID_ARG, "NULL argument");
+  std::copy(p->path_off.begin(), p->path_off.end(), out);
+  return SP_OK;
+}
+
+extern "C" const int32_t *sp_plan_path_offsets_device(const sp_plan *p) { return p ? p->dev.path_off : nullptr; }
+
+extern "C" int64_t sp_plan_visible_keys(const sp_plan *p, int32_t token, int32_t *out, int64_t cap) {
+  if (!p || (cap > 0 && !out)) return SP_ERR_INVALID_ARG;
+  if (token < 0 || token >= p->n_tokens) return SP_ERR_INVALID_ARG;
+  const int32_t g = p->tok_group[token];
+  if (g < 0) return 0;
+  const sp::RowGroup &rg = p->groups[g];
+  int64_t n = 0;
+  auto emit = [&](int32_t tok) { if (n < cap) out[n] = tok; ++n; };
+  for (int32_t r = 0; r < rg.n_ranges; ++r) {
+    const sp::KeyRange &kr = p->ranges[rg.range_off + r];
+    for (int32_t i = 0; i < kr.len; ++i) emit(kr.tok_start + i);
+  }
+  for (int32_t tok = rg.tok_start; tok <= token; ++tok) emit(tok);
+  return n;
+}
+
+extern "C" int64_t sp_plan_joined_keys(const sp_plan *p, int32_t prompt, const int32_t *kept, int32_t k,
+                                       int32_t *out, int64_t cap) {
+  if (!p || (k > 0 && !kept) || (cap > 0 && !out) || k < 0) return SP_ERR_INVALID_ARG;
+  if (prompt < 0 || prompt >= p->n_prompts) return SP_ERR_INVALID_ARG;
+  int64_t n = 0;
+  auto emit_ranges = [&](int32_t a, int32_t b) {
+    for (int32_t r = a; r < b; ++r)
+      for (int32_t i = 0; i < p->dec_ranges[r].len; ++i) {
+        if (n < cap) out[n] = p->dec_ranges[r].tok_start + i;
+        ++n;
+      }
+  };
+  emit_ranges(p->shared_rng_beg[prompt], p->shared_rng_end[prompt]);
+  const int32_t np = p->path_off[prompt + 1] - p->path_off[prompt];
+  for (int32_t j = 0; j < k; ++j) {
+    if (kept[j] < 0) continue;
+    if (kept[j] >= np) return SP_ERR_BAD_TABLE;
+    const int32_t slot = p->path_off[prompt] + kept[j];
+    emit_ranges(p->path_rng_beg[slot], p->path_rng_end[slot]);
+  }
+  return n;
+}
+
+// ---------------------------------------------------------------------------------------
+// a1 prefill
+// ---------------------------------------------------------------------------------------
+extern "C" sp_status sp_forkjoin_prefill(sp_ctx *ctx, const sp_plan *plan, const void *Q, const void *K,
+                                         const void *V, void *O, int64_t q_tok_stride, int64_t q_head_stride,
+                                         int64_t kv_tok_stride, int64_t kv_head_stride, float softmax_scale) {
+  if (!ctx) return fail(nullptr, SP_ERR_INVALID_ARG, "ctx is NULL");
+  if (!plan || !Q || !K || !V || !O) return fail(&ctx->err, SP_ERR_INVALID_ARG, "NULL argument");
+  if (plan->ctx != ctx) return fail(&ctx->err, SP_ERR_INVALID_ARG, "plan was not created on this context");
+  if (O == Q || O == K || O == V) return fail(&ctx->err, SP_ERR_INVALID_ARG, "O must not alias an input");
+  const int64_t d = plan->head_dim;
+  if (q_head_stride < d || kv_head_stride < d || q_tok_stride < q_head_stride * 1 || kv_tok_stride < kv_head_stride * 1 ||
+      q_tok_stride < d || kv_tok_stride < d)
+    return fail(&ctx->err, SP_ERR_INVALID_ARG, "strides smaller than head_dim");
+  const int64_t align = plan->dtype == SP_BF16 ? 8 : 4;   // 16-byte vector loads
+  if (q_tok_stride % align || q_head_stride % align || kv_tok_stride % align || kv_head_stride % align)
+    return fail(&ctx->err, SP_ERR_UNSUPPORTED, "strides must be multiples of %lld elements", (long long)align);
+  if ((reinterpret_cast<uintptr_t>(Q) | reinterpret_cast<uintptr_t>(K) | reinterpret_cast<uintptr_t>(V) |
+       reinterpret_cast<uintptr_t>(O)) & 15)
+    return fail(&ctx->err, SP_ERR_UNSUPPORTED, "Q, K, V, O must be 16-byte aligned");
+  if (!(softmax_scale > 0.f) || !std::isfinite(softmax_scale))
+    return fail(&ctx->err, SP_ERR_INVALID_ARG, "softmax_scale must be positive and finite");
+  sp::PrefillArgs a{Q, K, V, O, q_tok_stride, q_head_stride, kv_tok_stride, kv_head_stride, softmax_scale};
+  SP_HIP(ctx, hipSetDevice(ctx->device));
+  hipError_t e = plan->dtype == SP_BF16 ? sp::launch_prefill_bf16(plan, a, ctx->stream)
+                                        : sp::launch_prefill_f32(plan, a, ctx->stream);
+  if (e != hipSuccess) return fail(&ctx->err, SP_ERR_HIP, "prefill launch: %s", hipGetErrorString(e));
+  return SP_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// a2 saliency
+// ---------------------------------------------------------------------------------------
+extern "C" sp_status sp_path_saliency(sp_ctx *ctx, const void *logits, sp_dtype dtype, int64_t n_rows,
+                                      int64_t vocab, int64_t row_stride, const int32_t *target,
+                                      const int32_t *row_path, const float *prior, int32_t n_path_slots,
+                                      sp_saliency_mode mode, float *score) {
+  if (!ctx) return fail(nullptr, SP_ERR_INVALID_ARG, "ctx is NULL");
+  if (!logits || !target || !row_path || !score) return fail(&ctx->err, SP_ERR_INVALID_ARG, "NULL argument");
+  if (n_rows < 0 || vocab <= 0 || n_path_slots <= 0 || row_stride < vocab)
+    return fail(&ctx->err, SP_ERR_INVALID_ARG, "bad sizes (n_rows >= 0, vocab > 0, n_path_slots > 0, row_stride >= vocab)");
+  if (dtype != SP_F32 && dtype != SP_BF16) return fail(&ctx->err, SP_ERR_INVALID_ARG, "unknown dtype");
+  if (mode != SP_SALIENCY_SUM && mode != SP_SALIENCY_MEAN) return fail(&ctx->err, SP_ERR_INVALID_ARG, "unknown mode");
+  if (n_rows > (int64_t(1) << 30)) return fail(&ctx->err, SP_ERR_UNSUPPORTED, "n_rows above 2^30");
+  const int64_t esz = dtype == SP_BF16 ? 2 : 4;
+  if ((reinterpret_cast<uintptr_t>(logits) & 15) || (row_stride * esz) % 16)
+    return fail(&ctx->err, SP_ERR_UNSUPPORTED, "logits base and row stride must be 16-byte aligned");
+  SP_HIP(ctx, hipSetDevice(ctx->device));
+  sp_status st = ensure_ws(ctx, size_t(std::max<int64_t>(n_rows, 1)) * sizeof(float));
+  if (st != SP_OK) return st;
+  hipError_t e = sp::launch_saliency(logits, dtype, n_rows, vocab, row_stride, target, row_path, prior,
+                                     n_path_slots, int(mode), ctx->ws, score, ctx->stream);
+  if (e != hipSuccess) return fail(&ctx->err, SP_ERR_HIP, "saliency launch: %s", hipGetErrorString(e));
+  return SP_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// a3 top-k
+// ---------------------------------------------------------------------------------------
+extern "C" sp_status sp_prune_topk(sp_ctx *ctx, const float *score, const int32_t *path_off, int32_t n_prompts,
+                                   int32_t n_paths_max, int32_t k, int32_t *kept) {
+  if (!ctx) return fail(nullptr, SP_ERR_INVALID_ARG, "ctx is NULL");
+  if (!score || !path_off || !kept) return fail(&ctx->err, SP_ERR_INVALID_ARG, "NULL argument");
+  if (n_prompts <= 0 || k <= 0 || n_paths_max <= 0)
+    return fail(&ctx->err, SP_ERR_INVALID_ARG, "n_prompts, n_paths_max and k must be positive");
+  if (n_paths_max > 4096) return fail(&ctx->err, SP_ERR_UNSUPPORTED, "more than 4096 paths per prompt");
+  SP_HIP(ctx, hipSetDevice(ctx->device));
+  hipError_t e = sp::launch_topk(score, path_off, n_prompts, n_paths_max, k, kept, ctx->stream);
+  if (e != hipSuccess) return fail(&ctx->err, SP_ERR_HIP, "top-k launch: %s", hipGetErrorString(e));
+  return SP_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// a4 decode
+// ---------------------------------------------------------------------------------------
+extern "C" sp_status sp_pruned_decode(sp_ctx *ctx, const sp_plan *plan, const int32_t *kept, int32_t k,
+                                      const void *K_prefill, const void *V_prefill, int64_t kv_tok_stride,
+                                      int64_t kv_head_stride, void *K_resp, void *V_resp, float *pos_resp,
+                                      int32_t resp_capacity, const int32_t *resp_len, int32_t resp_len_add,
+                                      const float *new_pos, const void *q_new, const void *k_new,
+                                      const void *v_new, void *o_out, float softmax_scale) {
+  if (!ctx) return fail(nullptr, SP_ERR_INVALID_ARG, "ctx is NULL");
+  if (!plan || !K_prefill || !V_prefill || !K_resp || !V_resp || !q_new || !k_new || !v_new || !o_out)
+    return fail(&ctx->err, SP_ERR_INVALID_ARG, "NULL argument");
+  if (plan->ctx != ctx) return fail(&ctx->err, SP_ERR_INVALID_ARG, "plan was not created on this context");
+  if (k < 0 || (k > 0 && !kept)) return fail(&ctx->err, SP_ERR_INVALID_ARG, "k < 0 or kept is NULL");
+  if (resp_capacity <= 0 || resp_len_add < 0) return fail(&ctx->err, SP_ERR_INVALID_ARG, "bad response cache sizes");
+  if (plan->has_slopes && (!pos_resp || !new_pos))
+    return fail(&ctx->err, SP_ERR_INVALID_ARG, "plan has bias slopes: pos_resp and new_pos are required");
+  const int64_t d = plan->head_dim;
+  const int64_t align = plan->dtype == SP_BF16 ? 8 : 4;
+  if (kv_head_stride < d || kv_tok_stride < d || kv_tok_stride % align || kv_head_stride % align)
+    return fail(&ctx->err, SP_ERR_UNSUPPORTED, "bad kv strides");
+  if ((reinterpret_cast<uintptr_t>(K_prefill) | reinterpret_cast<uintptr_t>(V_prefill) |
+       reinterpret_cast<uintptr_t>(K_resp) | reinterpret_cast<uintptr_t>(V_resp) | reinterpret_cast<uintptr_t>(q_new) |
+       reinterpret_cast<uintptr_t>(k_new) | reinterpret_cast<uintptr_t>(v_new) | reinterpret_cast<uintptr_t>(o_out)) & 15)
+    return fail(&ctx->err, SP_ERR_UNSUPPORTED, "tensors must be 16-byte aligned");
+  if (!(softmax_scale > 0.f) || !std::isfinite(softmax_scale))
+    return fail(&ctx->err, SP_ERR_INVALID_ARG, "softmax_scale must be positive and finite");
+  // joined-cache range count bound: shared ranges + k * (largest per-path range count)
+  int32_t worst = 0;
+  for (int32_t b = 0; b < plan->n_prompts; ++b)
+    worst = std::max(worst, plan->shared_rng_end[b] - plan->shared_rng_beg[b] + k * plan->path_max_ranges[b]);
+  if (worst > 120) return fail(&ctx->err, SP_ERR_UNSUPPORTED, "joined cache has %d disjoint ranges (limit 120)", worst);
+  sp::DecodeArgs a{kept, k, K_prefill, V_prefill, kv_tok_stride, kv_head_stride, K_resp, V_resp, pos_resp,
+                   resp_capacity, resp_len, resp_len_add, new_pos, q_new, k_new, v_new, o_out, softmax_scale};
+  SP_HIP(ctx, hipSetDevice(ctx->device));
+  hipError_t e = sp::launch_decode(plan, a, ctx->stream);
+  if (e != hipSuccess) return fail(&ctx->err, SP_ERR_HIP, "decode launch: %s", hipGetErrorString(e));
+  return SP_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// Equilibrium positions (Sec. 3.2.2 Eq. 1; App. B.2 Eq. 3 and Alg. 1; query rule of Alg. 3)
+// ---------------------------------------------------------------------------------------
+extern "C" sp_status sp_equilibrium_positions(const sp_segtable *t, float *out) {
+  if (!out) return fail(nullptr, SP_ERR_INVALID_ARG, "tok_pos_out is NULL");
+  sp_segtable tt;
+  if (t) { tt = *t; tt.tok_pos = nullptr; tt.alibi_slopes = nullptr; }
+  sp_status st = validate_table(t ? &tt : nullptr, 0, nullptr);
+  if (st != SP_OK) return st;
+  const int32_t S = t->n_segments;
+  // harmonic mean of the lengths of each node's children: S = n / sum(1/len)   (Eq. 1)
+  std::vector<double> inv_sum(S, 0.0);
+  std::vector<int32_t> n_child(S, 0);
+  for (int32_t s = 0; s < S; ++s)
+    if (t->seg_parent[s] >= 0) {
+      inv_sum[t->seg_parent[s]] += 1.0 / double(t->seg_tok_len[s]);
+      n_child[t->seg_parent[s]] += 1;
+    }
+  std::vector<double> span_end(S, 0.0);   // position right after the segment's span
+  std::fill(out, out + t->n_tokens, 0.f);
+  for (int32_t s = 0; s < S; ++s) {
+    const int32_t par = t->seg_parent[s], len = t->seg_tok_len[s];
+    double start = 0.0, step = 1.0, span = double(len);
+    if (par >= 0) {
+      span = double(n_child[par]) / inv_sum[par];
+      step = span / double(len);
+      start = span_end[par];
+    }
+    for (int32_t i = 0; i < len; ++i) {
+      const double inc = step * double(i);        // ArangePositions (Eq. 3): start + i * step
+      out[t->seg_tok_start[s] + i] = static_cast<float>(start + inc);
+    }
+    span_end[s] = start + span;
+  }
+  return SP_OK;
+}

@@ -1,0 +1,135 @@
+// Internal declarations shared by the translation units of libsp.so (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "sp.h"
+
+namespace sp {
+
+constexpr int kMaxRanges = 32;     // ancestor key ranges per row group (after merging neighbours)
+constexpr int kPrefillThreads = 256;
+
+// A run of segments fused on the query side: child segments that are packed directly behind
+// their parent continue the parent's causal sequence (Sec. 3.2: a chain is a classical prompt).
+// Rows [tok_start, tok_start+len) see: the ancestor ranges (all keys), then own rows causally.
+struct RowGroup {
+  int32_t tok_start;
+  int32_t len;
+  int32_t range_off;   // first ancestor range (root-to-leaf order)
+  int32_t n_ranges;
+  int32_t anc_keys;    // total keys in the ancestor ranges
+  int32_t prompt;
+};
+
+struct KeyRange {
+  int32_t tok_start;
+  int32_t len;
+};
+
+// One prefill work item: a tile of query rows of one row group, for one group of query heads.
+struct WorkItem {
+  int32_t group;       // RowGroup index
+  int32_t row0;        // first row of the tile inside the group
+  int32_t head0;       // first query head handled by the workgroup
+  int32_t pad;
+};
+
+// Device-side view of a plan (plain pointers, passed by value to kernels).
+struct PlanDev {
+  const RowGroup *groups;
+  const KeyRange *ranges;
+  const WorkItem *items;
+  const int32_t *tok_group;      // [n_tokens] row group of each token, -1 = uncovered
+  const float *tok_pos;          // [n_tokens] or nullptr
+  const float *slopes;           // [n_q_heads] or nullptr
+  // decode tables
+  const int32_t *path_off;       // [n_prompts+1]
+  const int32_t *shared_rng_beg; // [n_prompts] first/last+1 range of the shared segments
+  const int32_t *shared_rng_end; // [n_prompts]
+  const int32_t *path_rng_beg;   // [n_slots] first/last+1 range of each path slot
+  const int32_t *path_rng_end;   // [n_slots]
+  const KeyRange *dec_ranges;
+  int32_t n_items;
+  int32_t n_tokens;
+  int32_t n_prompts;
+  int32_t n_q_heads, n_kv_heads, head_dim;
+};
+
+}  // namespace sp
+
+struct sp_ctx {
+  int device = 0;
+  hipStream_t stream = nullptr;
+  std::string err;
+  float *ws = nullptr;        // workspace (per-row log-likelihoods)
+  size_t ws_bytes = 0;
+};
+
+struct sp_plan {
+  sp_ctx *ctx = nullptr;      // nullptr: host-only plan
+  int32_t n_prompts = 0, n_segments = 0, n_tokens = 0, n_slots = 0;
+  int32_t n_q_heads = 0, n_kv_heads = 0, head_dim = 0;
+  sp_dtype dtype = SP_F32;
+  int32_t heads_per_wg = 1;   // query heads stacked in one prefill workgroup
+  int32_t tile_rows = 0;      // token rows per prefill tile
+  int32_t n_tiles = 0;
+  int32_t max_ranges = 0;
+  int32_t max_dec_ranges = 0; // largest joined-cache range count bound per prompt (shared + per-path max)
+  int64_t visible_pairs = 0;
+  bool has_pos = false, has_slopes = false;
+  // host copies
+  std::vector<int32_t> prompt_seg_off, seg_tok_start, seg_tok_len, seg_parent, seg_path;
+  std::vector<sp::RowGroup> groups;
+  std::vector<sp::KeyRange> ranges;
+  std::vector<sp::WorkItem> items;
+  std::vector<int32_t> tok_group;
+  std::vector<int32_t> path_off, shared_rng_beg, shared_rng_end, path_rng_beg, path_rng_end;
+  std::vector<sp::KeyRange> dec_ranges;
+  std::vector<int32_t> path_max_ranges;  // per prompt: max ranges of any single path
+  // device copies (one allocation)
+  void *dev_blob = nullptr;
+  sp::PlanDev dev{};
+};
+
+namespace sp {
+
+// Kernel launchers (defined next to their kernels).  All return hipError_t from the launch.
+struct PrefillArgs {
+  const void *Q, *K, *V;
+  void *O;
+  int64_t q_tok_stride, q_head_stride, kv_tok_stride, kv_head_stride;
+  float scale;
+};
+hipError_t launch_prefill_bf16(const sp_plan *plan, const PrefillArgs &a, hipStream_t s);
+hipError_t launch_prefill_f32(const sp_plan *plan, const PrefillArgs &a, hipStream_t s);
+
+hipError_t launch_saliency(const void *logits, sp_dtype dt, int64_t n_rows, int64_t vocab, int64_t row_stride,
+                           const int32_t *target, const int32_t *row_path, const float *prior,
+                           int32_t n_slots, int mode, float *lp_ws, float *score, hipStream_t s);
+
+hipError_t launch_topk(const float *score, const int32_t *path_off, int32_t n_prompts, int32_t n_paths_max,
+                       int32_t k, int32_t *kept, hipStream_t s);
+
+struct DecodeArgs {
+  const int32_t *kept;
+  int32_t k;
+  const void *Kp, *Vp;
+  int64_t kv_tok_stride, kv_head_stride;
+  void *Kr, *Vr;
+  float *pos_resp;
+  int32_t resp_capacity;
+  const int32_t *resp_len;
+  int32_t resp_len_add;
+  const float *new_pos;
+  const void *q_new, *k_new, *v_new;
+  void *o_out;
+  float scale;
+};
+hipError_t launch_decode(const sp_plan *plan, const DecodeArgs &a, hipStream_t s);
+
+}  // namespace sp

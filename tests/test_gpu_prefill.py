@@ -1,0 +1,148 @@
+"""GPU parity of sp_forkjoin_prefill against the CPU oracle (through the C ABI)."""
+import math
+import zlib
+
+import numpy as np
+import pytest
+import torch
+
+import sp_synth
+from oracle import sp_oracle as orc
+from paper_2404_06910_amd import binding as B
+
+from gpu_util import check_attn, covered_tokens, dev, make_plan, run_prefill
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = B.Context(0)
+    yield c
+    c.close()
+
+
+def _oracle(st, q, k, v, scale, **kw):
+    return orc.forkjoin_prefill(q, k, v, st.prompt_seg_off, st.seg_tok_start, st.seg_tok_len, st.seg_parent, scale, **kw)
+
+
+def _rand(rng, T, Hq, Hkv, d, dtype):
+    f = lambda *s: sp_synth.round_to_dtype(rng.standard_normal(s, dtype=np.float32), dtype)
+    return f(T, Hq, d), f(T, Hkv, d), f(T, Hkv, d)
+
+
+def test_config1_tiny_fp32_all_elements(ctx):
+    print("case: c1_tiny_f32", flush=True)
+    inp = sp_synth.make_inputs(sp_synth.WORKLOADS["c1_tiny_f32"], with_logits=False, with_decode=False)
+    got, _ = run_prefill(ctx, inp.st, inp.q, inp.k, inp.v, "f32")
+    ref = _oracle(inp.st, inp.q, inp.k, inp.v, 1 / 8.0)
+    check_attn(got, ref, "f32", "c1")
+    # with linear distance bias on classical positions
+    slopes = sp_synth.geometric_slopes(4)
+    got, _ = run_prefill(ctx, inp.st, inp.q, inp.k, inp.v, "f32", tok_pos=inp.tok_pos, slopes=slopes)
+    ref = _oracle(inp.st, inp.q, inp.k, inp.v, 1 / 8.0, tok_pos=inp.tok_pos, alibi_slopes=slopes)
+    check_attn(got, ref, "f32", "c1+bias")
+
+
+SMALL = [
+    # (dtype, Hq, Hkv, d, P, doc_lens per prompt, Lq, packing, bias)
+    ("bf16", 2, 2, 128, 16, [[32, 32]], 8, "interleaved", False),
+    ("bf16", 4, 4, 128, 64, [[128, 100, 1, 33], [5, 200]], 24, "interleaved", False),     # ragged, path of length 1
+    ("bf16", 8, 2, 128, 37, [[65, 31, 96]], 1, "interleaved", True),                      # GQA 4, Lq = 1, bias
+    ("bf16", 4, 2, 64, 50, [[70, 129], [64]], 7, "grouped", False),                       # GQA 2, d = 64, grouped
+    ("bf16", 8, 1, 64, 3, [[40, 41, 42]], 9, "grouped", True),                            # GQA 8
+    ("bf16", 3, 3, 128, 130, [[300]], 31, "interleaved", False),                          # one doc = causal, 461 rows
+    ("bf16", 6, 2, 128, 20, [[45, 77]], 5, "interleaved", False),                         # GQA 3 (odd group)
+    ("f32", 4, 2, 128, 33, [[47, 20], [64, 3, 9]], 6, "grouped", True),
+    ("f32", 2, 2, 64, 1, [[1]], 1, "interleaved", False),                                 # degenerate: 3 tokens
+]
+
+
+@pytest.mark.parametrize("case", SMALL, ids=lambda c: "%s-h%d/%d-d%d-P%d-%s%s" % (c[0], c[1], c[2], c[3], c[4], c[7][:3], "-b" if c[8] else ""))
+def test_small_shapes_all_elements(ctx, case):
+    dtype, Hq, Hkv, d, P, lens, Lq, packing, bias = case
+    print("case:", case, flush=True)
+    rng = np.random.default_rng(zlib.crc32(str(case).encode()))
+    st = sp_synth.forkjoin_segtable(P, lens, Lq, packing)
+    q, k, v = _rand(rng, st.n_tokens, Hq, Hkv, d, dtype)
+    pos = slopes = None
+    if bias:
+        # equilibrium positions from the oracle (ragged documents -> real-valued positions)
+        pos = np.zeros(st.n_tokens, np.float32)
+        for b, ll in enumerate(lens):
+            a, dd, qq = orc.equilibrium_positions(P, ll, Lq)
+            s0 = st.seg_tok_start[st.preamble_seg[b]]; pos[s0:s0 + P] = a
+            for i in range(len(ll)):
+                slot = st.path_off[b] + i
+                s0 = st.seg_tok_start[st.doc_seg[slot]]; pos[s0:s0 + ll[i]] = dd[i]
+                s0 = st.seg_tok_start[st.query_seg[slot]]; pos[s0:s0 + Lq] = qq
+        slopes = sp_synth.geometric_slopes(Hq)
+    got, plan = run_prefill(ctx, st, q, k, v, dtype, tok_pos=pos, slopes=slopes)
+    ref = _oracle(st, q, k, v, 1 / math.sqrt(d), tok_pos=pos, alibi_slopes=slopes)
+    check_attn(got, ref, dtype, str(case))
+    # bitwise determinism (no float atomics, fixed reduction order)
+    again, _ = run_prefill(ctx, st, q, k, v, dtype, tok_pos=pos, slopes=slopes, plan=plan)
+    assert np.array_equal(got, again, equal_nan=True)
+
+
+def test_general_tree_with_gaps_and_untouched_rows(ctx):
+    # deeper chains, several shared segments, scrambled packing with uncovered tokens
+    from test_host_plan import _random_table
+    for seed in (11, 12):
+        rng = np.random.default_rng(seed)
+        t = _random_table(rng, 3, scramble=True)
+        T = t["n_tokens"]
+        q, k, v = _rand(rng, T, 4, 2, 64, "bf16")
+        print("case: random tree seed", seed, "tokens", T, flush=True)
+        plan = B.Plan(ctx, t["prompt_seg_off"], t["seg_tok_start"], t["seg_tok_len"], t["seg_parent"], t["seg_path"], T,
+                      4, 2, 64, B.SP_BF16)
+        Q, K, V = dev(q, "bf16"), dev(k, "bf16"), dev(v, "bf16")
+        O = torch.full_like(Q, 7.0)
+        ctx.sp_forkjoin_prefill(plan, Q, K, V, O, 0.125)
+        torch.cuda.synchronize()
+        got = O.float().cpu().numpy()
+        ref = orc.forkjoin_prefill(q, k, v, t["prompt_seg_off"], t["seg_tok_start"], t["seg_tok_len"], t["seg_parent"], 0.125)
+        check_attn(got, ref, "bf16", "tree %d" % seed)
+        assert np.all(got[np.isnan(ref)] == 7.0)            # uncovered tokens are left untouched
+
+
+def test_independence_of_paths_is_bitwise(ctx):
+    rng = np.random.default_rng(5)
+    st = sp_synth.forkjoin_segtable(64, [[128, 90, 128]], 24)
+    q, k, v = _rand(rng, st.n_tokens, 4, 4, 128, "bf16")
+    base, plan = run_prefill(ctx, st, q, k, v, "bf16")
+    lo = int(st.seg_tok_start[st.doc_seg[1]]); hi = int(st.seg_tok_start[st.query_seg[1]] + 24)
+    q2, k2, v2 = q.copy(), k.copy(), v.copy()
+    k2[lo:hi] = -k2[lo:hi]; v2[lo:hi] = v2[lo:hi] * 2; q2[lo:hi] = 0
+    pert, _ = run_prefill(ctx, st, q2, k2, v2, "bf16", plan=plan)
+    others = np.ones(st.n_tokens, bool); others[lo:hi] = False
+    assert np.array_equal(base[others], pert[others])
+
+
+FULL = ["c2_mha7b_bf16", "c3_ragged_bf16", "c4_gqa_bf16"]
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_sampled_prompt_head_pairs(ctx, name):
+    """Full workload shape in the launch configuration the benchmark times; the oracle
+    evaluates sampled (prompt, head) pairs completely (all tokens of the prompt)."""
+    wl = sp_synth.WORKLOADS[name]
+    print("case:", name, flush=True)
+    inp = sp_synth.make_inputs(wl, with_logits=False, with_decode=False)
+    st = inp.st
+    got, plan = run_prefill(ctx, st, inp.q, inp.k, inp.v, "bf16")
+    assert not np.isnan(got[covered_tokens(st)]).any()
+    rng = np.random.default_rng(1)
+    n_samples = 3 if name == "c3_ragged_bf16" else 5
+    scale = 1 / math.sqrt(wl.head_dim)
+    for _ in range(n_samples):
+        b = int(rng.integers(0, wl.n_prompts)); h = int(rng.integers(0, wl.n_q_heads))
+        ref = _oracle(st, inp.q, inp.k, inp.v, scale, prompts=[b], heads=[h])
+        check_attn(got, ref, "bf16", "%s b%d h%d" % (name, b, h))
+    # property at full size: constant V rows give that constant back whatever the mask (softmax sums to 1)
+    V1 = torch.ones(inp.v.shape, dtype=torch.bfloat16, device="cuda") * 0.5
+    Q, K = dev(inp.q, "bf16"), dev(inp.k, "bf16")
+    O = torch.empty_like(Q)
+    ctx.sp_forkjoin_prefill(plan, Q, K, V1, O, scale)
+    torch.cuda.synchronize()
+    assert torch.all((O.float() - 0.5).abs() <= 2 ** -8)
