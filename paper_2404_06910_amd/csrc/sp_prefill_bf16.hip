@@ -28,9 +28,10 @@
 namespace sp {
 
 constexpr int kBK = 64;            // keys per LDS stage
+typedef bf16x4 __attribute__((address_space(3))) lds_bf16x4;
 
 template <int D, int HPW, bool BIAS>
-__global__ __launch_bounds__(256) void prefill_bf16_kernel(PlanDev pd, const __bf16 *__restrict__ Q,
+__global__ __launch_bounds__(256, 2) void prefill_bf16_kernel(PlanDev pd, const __bf16 *__restrict__ Q,
                                                            const __bf16 *__restrict__ K,
                                                            const __bf16 *__restrict__ V, __bf16 *__restrict__ O,
                                                            int64_t q_ts, int64_t q_hs, int64_t kv_ts,
@@ -97,6 +98,8 @@ __global__ __launch_bounds__(256) void prefill_bf16_kernel(PlanDev pd, const __b
 #pragma unroll
     for (int j = 0; j < NJ; ++j) qf[j] = *reinterpret_cast<const bf16x8 *>(qp + 16 * j);
   }
+  const int tr_row = (lane & 15) >> 2;                     // transpose-read source: key row within 4
+  const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);   // and first of 4 dims within 32
   const float scale2 = scale * kLog2e;
   float slope2 = 0.f, pos_q = 0.f;
   if (BIAS) {
@@ -201,10 +204,12 @@ __global__ __launch_bounds__(256) void prefill_bf16_kernel(PlanDev pd, const __b
       for (int c = 0; c < NC; ++c) {
 #pragma unroll
         for (int mm = 0; mm < 2; ++mm) {
-          bf16x8 a;
-#pragma unroll
-          for (int jj = 0; jj < 8; ++jj)
-            a[jj] = Vs[buf][32 * sub + 16 * mm + 8 * (jj / 4) + 4 * half + (jj % 4)][32 * c + l32];
+          // V^T fragment through the LDS transpose read: a 16-lane group hands in a 4-key x 16-dim
+          // block (lane s: key s/4, dims 4*(s%4)..+3) and lane i receives dim i of the 4 keys.
+          const __bf16 *vp = &Vs[buf][32 * sub + 16 * mm + 4 * half + tr_row][32 * c + tr_col];
+          const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)vp);
+          const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(vp + 8 * LDK));
+          const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
           o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[mm], o[c], 0, 0, 0);
         }
       }
