@@ -20,7 +20,7 @@ SOURCES = ["sp_api.hip", "sp_prefill_bf16.hip", "sp_prefill_f32.hip", "sp_salien
            "sp_decode.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=on",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+         "-I" + os.path.join(ROOT, "include"), "-I" + CSRC] + os.environ.get("SP_EXTRA_FLAGS", "").split()
 
 
 def _hipcc() -> str:

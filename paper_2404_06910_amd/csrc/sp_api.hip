@@ -242,10 +242,11 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
   }
 
   // --- prefill work list.  Query heads that share a KV head are stacked in one workgroup
-  // (4 waves): 4, 2 or 1 heads per workgroup, each wave owning 32 token rows of one head.
+  // (4 waves for 4 heads, else 2 waves), each wave owning 32 token rows of one head.
   const int32_t G = n_q_heads / n_kv_heads;
   p->heads_per_wg = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
-  p->tile_rows = 32 * (4 / p->heads_per_wg);
+  p->waves_per_wg = p->heads_per_wg == 4 ? 4 : 2;
+  p->tile_rows = 32 * (p->waves_per_wg / p->heads_per_wg);
   const int32_t n_hg = n_q_heads / p->heads_per_wg;
   {
     size_t g = 0;
@@ -259,7 +260,39 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
       // same K/V rows run close together in time and, after the XCD remap in the kernel, on
       // the same L2.
       for (int32_t hg = 0; hg < n_hg; ++hg)
-        for (auto &tl : tiles) p->items.push_back({tl.first, tl.second, hg * p->heads_per_wg, 0});
+        for (auto &tl : tiles) {
+          const sp::RowGroup &rg = p->groups[tl.first];
+          sp::WorkItem w{};
+          w.tok_start = rg.tok_start; w.row0 = tl.second;
+          w.n_rows = std::min(p->tile_rows, rg.len - tl.second);
+          w.anc_keys = rg.anc_keys; w.range_off = rg.range_off; w.n_ranges = rg.n_ranges;
+          w.head0 = hg * p->heads_per_wg;
+          w.r0_start = rg.n_ranges > 0 ? p->ranges[rg.range_off].tok_start : 0;
+          p->items.push_back(w);
+        }
+    }
+  }
+  // Persistent workgroups: two per compute unit, each owning a contiguous, cost-balanced slice of
+  // the work list (cost = LDS stages streamed: one for Q plus the K/V stages, plus the epilogue).
+  {
+    int n_cu = 256;
+    if (ctx) {
+      hipDeviceProp_t prop;
+      if (hipGetDeviceProperties(&prop, ctx->device) == hipSuccess && prop.multiProcessorCount > 0)
+        n_cu = prop.multiProcessorCount;
+    }
+    const int32_t stage_keys = 16 * p->waves_per_wg;
+    const int32_t n_wg = (((8 / p->waves_per_wg) * n_cu + 7) / 8) * 8;   // 8 waves per compute unit
+    int64_t total = 0;
+    auto stages = [&](const sp::WorkItem &w) { return (w.anc_keys + w.row0 + w.n_rows + stage_keys - 1) / stage_keys; };
+    for (auto &w : p->items) total += 2 + stages(w);
+    p->wg_begin.assign(n_wg + 1, static_cast<int32_t>(p->items.size()));
+    p->wg_begin[0] = 0;
+    int64_t acc = 0;
+    int32_t c = 1;
+    for (size_t i = 0; i < p->items.size() && c < n_wg; ++i) {
+      acc += 2 + stages(p->items[i]);
+      while (c < n_wg && acc * n_wg >= total * c) p->wg_begin[c++] = static_cast<int32_t>(i + 1);
     }
   }
 
@@ -301,7 +334,7 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
     if (t->alibi_slopes) slopes.assign(t->alibi_slopes, t->alibi_slopes + n_q_heads);
     size_t off = 0;
     const size_t o_groups = blob_reserve(off, p->groups), o_ranges = blob_reserve(off, p->ranges),
-                 o_items = blob_reserve(off, p->items), o_tokg = blob_reserve(off, p->tok_group),
+                 o_items = blob_reserve(off, p->items), o_wgb = blob_reserve(off, p->wg_begin), o_tokg = blob_reserve(off, p->tok_group),
                  o_pos = blob_reserve(off, pos), o_slopes = blob_reserve(off, slopes),
                  o_poff = blob_reserve(off, p->path_off), o_sb = blob_reserve(off, p->shared_rng_beg),
                  o_se = blob_reserve(off, p->shared_rng_end), o_pb = blob_reserve(off, p->path_rng_beg),
@@ -319,6 +352,7 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
     up(o_groups, p->groups.data(), p->groups.size() * sizeof(sp::RowGroup));
     up(o_ranges, p->ranges.data(), p->ranges.size() * sizeof(sp::KeyRange));
     up(o_items, p->items.data(), p->items.size() * sizeof(sp::WorkItem));
+    up(o_wgb, p->wg_begin.data(), p->wg_begin.size() * 4);
     up(o_tokg, p->tok_group.data(), p->tok_group.size() * 4);
     up(o_pos, pos.data(), pos.size() * 4);
     up(o_slopes, slopes.data(), slopes.size() * 4);
@@ -347,6 +381,8 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
     d.path_rng_end = reinterpret_cast<const int32_t *>(base + o_pe);
     d.dec_ranges = reinterpret_cast<const sp::KeyRange *>(base + o_dr);
     d.n_items = static_cast<int32_t>(p->items.size());
+    d.wg_begin = reinterpret_cast<const int32_t *>(base + o_wgb);
+    d.n_wg = static_cast<int32_t>(p->wg_begin.size()) - 1;
     d.n_tokens = p->n_tokens;
     d.n_prompts = p->n_prompts;
     d.n_q_heads = n_q_heads; d.n_kv_heads = n_kv_heads; d.head_dim = head_dim;
@@ -432,6 +468,8 @@ extern "C" sp_status sp_forkjoin_prefill(sp_ctx *ctx, const sp_plan *plan, const
   if (q_head_stride < d || kv_head_stride < d || q_tok_stride < q_head_stride * 1 || kv_tok_stride < kv_head_stride * 1 ||
       q_tok_stride < d || kv_tok_stride < d)
     return fail(&ctx->err, SP_ERR_INVALID_ARG, "strides smaller than head_dim");
+  if (q_tok_stride >= (int64_t(1) << 31) || kv_tok_stride >= (int64_t(1) << 31))
+    return fail(&ctx->err, SP_ERR_UNSUPPORTED, "token strides must be below 2^31 elements");
   const int64_t align = plan->dtype == SP_BF16 ? 8 : 4;   // 16-byte vector loads
   if (q_tok_stride % align || q_head_stride % align || kv_tok_stride % align || kv_head_stride % align)
     return fail(&ctx->err, SP_ERR_UNSUPPORTED, "strides must be multiples of %lld elements", (long long)align);

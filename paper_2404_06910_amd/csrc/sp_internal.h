@@ -32,11 +32,16 @@ struct KeyRange {
 };
 
 // One prefill work item: a tile of query rows of one row group, for one group of query heads.
+// Self-contained (one 32-byte scalar load), so a workgroup never chases pointers between items.
 struct WorkItem {
-  int32_t group;       // RowGroup index
+  int32_t tok_start;   // first packed token of the row group
   int32_t row0;        // first row of the tile inside the group
+  int32_t n_rows;      // token rows in the tile (1 .. tile_rows)
+  int32_t anc_keys;    // keys in the ancestor ranges
+  int32_t range_off;   // first ancestor range
+  int32_t n_ranges;
   int32_t head0;       // first query head handled by the workgroup
-  int32_t pad;
+  int32_t r0_start;    // first token of ancestor range 0 (the only one when n_ranges == 1)
 };
 
 // Device-side view of a plan (plain pointers, passed by value to kernels).
@@ -44,6 +49,7 @@ struct PlanDev {
   const RowGroup *groups;
   const KeyRange *ranges;
   const WorkItem *items;
+  const int32_t *wg_begin;       // [n_wg+1] contiguous slice of the work list per persistent workgroup
   const int32_t *tok_group;      // [n_tokens] row group of each token, -1 = uncovered
   const float *tok_pos;          // [n_tokens] or nullptr
   const float *slopes;           // [n_q_heads] or nullptr
@@ -55,6 +61,7 @@ struct PlanDev {
   const int32_t *path_rng_end;   // [n_slots]
   const KeyRange *dec_ranges;
   int32_t n_items;
+  int32_t n_wg;
   int32_t n_tokens;
   int32_t n_prompts;
   int32_t n_q_heads, n_kv_heads, head_dim;
@@ -76,6 +83,7 @@ struct sp_plan {
   int32_t n_q_heads = 0, n_kv_heads = 0, head_dim = 0;
   sp_dtype dtype = SP_F32;
   int32_t heads_per_wg = 1;   // query heads stacked in one prefill workgroup
+  int32_t waves_per_wg = 4;   // waves (32-row blocks) per prefill workgroup
   int32_t tile_rows = 0;      // token rows per prefill tile
   int32_t n_tiles = 0;
   int32_t max_ranges = 0;
@@ -87,6 +95,7 @@ struct sp_plan {
   std::vector<sp::RowGroup> groups;
   std::vector<sp::KeyRange> ranges;
   std::vector<sp::WorkItem> items;
+  std::vector<int32_t> wg_begin;
   std::vector<int32_t> tok_group;
   std::vector<int32_t> path_off, shared_rng_beg, shared_rng_end, path_rng_beg, path_rng_end;
   std::vector<sp::KeyRange> dec_ranges;
