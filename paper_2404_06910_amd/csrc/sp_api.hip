@@ -242,10 +242,10 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
   }
 
   // --- prefill work list.  Query heads that share a KV head are stacked in one workgroup
-  // of 4 waves, each wave owning 32 token rows of one head.
+  // (4 waves for 4 heads, else 2 waves), each wave owning 32 token rows of one head.
   const int32_t G = n_q_heads / n_kv_heads;
   p->heads_per_wg = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
-  p->waves_per_wg = 4;
+  p->waves_per_wg = p->heads_per_wg == 4 ? 4 : 2;
   p->tile_rows = 32 * (p->waves_per_wg / p->heads_per_wg);
   const int32_t n_hg = n_q_heads / p->heads_per_wg;
   {
@@ -281,17 +281,17 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
       if (hipGetDeviceProperties(&prop, ctx->device) == hipSuccess && prop.multiProcessorCount > 0)
         n_cu = prop.multiProcessorCount;
     }
-    const int32_t stage_keys = 32;
-    const int32_t n_wg = ((2 * n_cu + 7) / 8) * 8;         // two 4-wave workgroups per compute unit
+    const int32_t stage_keys = 16 * p->waves_per_wg;
+    const int32_t n_wg = (((8 / p->waves_per_wg) * n_cu + 7) / 8) * 8;   // 8 waves per compute unit
     int64_t total = 0;
     auto stages = [&](const sp::WorkItem &w) { return (w.anc_keys + w.row0 + w.n_rows + stage_keys - 1) / stage_keys; };
-    for (auto &w : p->items) total += 3 + stages(w);
+    for (auto &w : p->items) total += 2 + stages(w);
     p->wg_begin.assign(n_wg + 1, static_cast<int32_t>(p->items.size()));
     p->wg_begin[0] = 0;
     int64_t acc = 0;
     int32_t c = 1;
     for (size_t i = 0; i < p->items.size() && c < n_wg; ++i) {
-      acc += 3 + stages(p->items[i]);
+      acc += 2 + stages(p->items[i]);
       while (c < n_wg && acc * n_wg >= total * c) p->wg_begin[c++] = static_cast<int32_t>(i + 1);
     }
   }

@@ -9,16 +9,14 @@
 // every 32-key block is either fully visible, on the diagonal (per-element mask) or never
 // enumerated at all.  Only the loader knows that the keys come from disjoint token ranges.
 //
-// Workgroup = 4 waves = 4 blocks of 32 query rows: HPW query heads that share one KV head times
-// 4/HPW blocks of 32 tokens; three workgroups per compute unit.  Workgroups are persistent: each
-// owns a contiguous slice of the work list and streams one unbroken sequence of 64-row LDS stages
-// through a ring of three slots -- per item its Q tile (128 rows = two stages, the second only if
-// it has rows), then its K/V tiles of 32 keys (32 K rows + 32 V rows).  Stages are filled by
-// LDS-DMA (global_load_lds_dwordx4: global memory straight into LDS, no staging registers) issued
-// two stages ahead of the math, also across item boundaries; one barrier per stage.  LDS rows are
-// unpadded; 16-byte chunks are XOR-swizzled on the global-address side of the DMA so that both the
-// row reads of K (ds_read_b128) and the transpose reads of V (ds_read_b64_tr_b16) are free of bank
-// conflicts.
+// Workgroup = NW waves = NW blocks of 32 query rows: HPW query heads that share one KV head times
+// NW/HPW blocks of 32 tokens (4 waves when 4 heads share a KV head; else 2 waves, so that the
+// causal imbalance between early and late row blocks stays inside a pair).  Workgroups are
+// persistent: each owns a contiguous, cost-balanced slice of the work list (staged in LDS) and
+// streams one unbroken sequence of LDS stages through a double buffer -- for every item first its
+// Q tile (32*NW rows = one stage), then its K/V tiles of 16*NW keys -- so the global loads of the
+// next stage (also across item boundaries) are in flight behind the current stage's math and no
+// item pays a cold start.  O^T tiles leave through LDS as whole 16-byte chunks of contiguous rows.
 //
 // Per wave and 32-key block, with the v_mfma_f32_32x32x16_bf16 tile shape:
 //   S^T[key, row]  = K[key, :] . Q[row, :]      A = K fragment (LDS), B = Q fragment (registers)
@@ -29,18 +27,19 @@
 // and the exponentiated scores are already in the B-operand layout of the second product: the
 // k-slots of that MFMA are simply bound to the keys this lane holds, and the V fragment is read
 // with the same key order.
-#include <cstdlib>
 #include "sp_device.h"
 #include "sp_internal.h"
 
 namespace sp {
 
 constexpr int kItemBatch = 32;     // work items staged in LDS at a time
-#ifndef SP_OCC
-#define SP_OCC 2
+#ifndef SP_PADK
+#define SP_PADK 8
+#endif
+#ifndef SP_PADV
+#define SP_PADV 8
 #endif
 typedef bf16x4 __attribute__((address_space(3))) lds_bf16x4;
-typedef unsigned char __attribute__((address_space(3))) lds_byte;
 
 // max / sum partner exchange between lane L and lane L^32 (v_permlane32_swap)
 __device__ __forceinline__ float xhalf_max(float x) {
@@ -52,48 +51,32 @@ __device__ __forceinline__ float xhalf_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// LDS-DMA: every lane moves 16 bytes from its global address to LDS byte (lds_base + 16 * lane).
-// The compiler does not track these loads; completion is awaited with explicit s_waitcnt vmcnt.
-__device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory", "m0");
-}
-
-template <int D, int HPW, bool BIAS>
-__global__ __launch_bounds__(256, SP_OCC) void prefill_bf16_kernel(PlanDev pd, const __bf16 *__restrict__ Q,
+template <int D, int HPW, int NW, bool BIAS>
+__global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, const __bf16 *__restrict__ Q,
                                                                   const __bf16 *__restrict__ K,
                                                                   const __bf16 *__restrict__ V,
                                                                   __bf16 *__restrict__ O, uint32_t q_ts,
                                                                   uint32_t q_hs, uint32_t kv_ts, uint32_t kv_hs,
-                                                                  float scale, int dbg) {
-  constexpr int NW = 4;                    // waves
+                                                                  float scale) {
   constexpr int T = 64 * NW;               // threads
-  constexpr int BK = 32;                   // keys per K/V stage; a stage holds 2*BK = 64 rows
-  constexpr int ROWB = D * 2;              // bytes per LDS row (unpadded)
+  constexpr int BK = 16 * NW;              // keys per K/V stage; a stage holds 2*BK = 32*NW rows
+  constexpr int LDK = D + SP_PADK;         // padded LDS rows of the K half (16-byte row reads)
+  constexpr int LDV = D + SP_PADV;         // and of the V half (transpose reads of 4 keys x 16 dims)
   constexpr int CPR = D / 8;               // 16-byte chunks per row
-  constexpr int RPC = 256 / ROWB;          // rows per 256-byte bank cycle (1 or 2)
-  constexpr int RG = 64 / CPR;             // rows moved by one wave-wide DMA instruction (4 or 8)
-  constexpr int WROWS = 2 * BK / NW;       // stage rows filled by one wave (16)
-  constexpr int NDMA = WROWS / RG;         // DMA instructions per wave and stage (4 or 2)
-  constexpr int HALFB = BK * ROWB;         // bytes of the K half (= of the V half) of a stage
-  constexpr int STAGEB = 2 * HALFB;
-  constexpr int NS = 3;                    // ring slots; loads run NS-1 = 2 stages ahead
+  constexpr int RPP = T / CPR;             // rows covered by one pass of all threads
+  constexpr int LOADS = BK / RPP;          // passes per half stage
   constexpr int NJ = D / 16;               // MFMAs along head_dim for S
   constexpr int NC = D / 32;               // 32-wide output blocks of O^T
+  static_assert(NW % HPW == 0 && BK % 32 == 0 || BK == 32, "tile shape");
 
-  // ring[slot]: BK K rows then BK V rows (half a Q tile uses the same 2*BK rows)
-  __shared__ __attribute__((aligned(1024))) unsigned char ring[NS * STAGEB];
-  __shared__ float Ps[NS][BK];
+  // A stage is BK K rows + BK V rows; a Q tile (2*BK rows) uses the K half for rows 0..BK and the
+  // V half for rows BK..2BK.
+  __shared__ __attribute__((aligned(16))) __bf16 stK[2][BK][LDK];
+  __shared__ __attribute__((aligned(16))) __bf16 stV[2][BK][LDV];
+  // row r of the 2*BK-row view of a stage
+  auto srow = [&](int buf, int r) -> __bf16 * { return r < BK ? &stK[buf][r][0] : &stV[buf][r - BK][0]; };
+  __shared__ float Ps[2][BK];
   __shared__ __attribute__((aligned(16))) WorkItem s_items[kItemBatch];
-
-  // Chunk swizzles (16-byte chunk index XOR f(row)), row = index inside the K half or the V half:
-  // K half: 16 consecutive rows reading the same chunk hit 16 different bank groups;
-  // V half: the 4 rows x 32 bytes of a transpose read, and its neighbour 16 dims further, are disjoint.
-  auto fK = [](int row) { return (row / RPC) % CPR; };
-  auto fV = [](int row) { return 4 * ((row / RPC) % (CPR / 4)); };
-  // byte offset of chunk ch of stage row r (0 .. 2*BK) inside a slot
-  auto row_chunk = [&](int r, int ch) -> int {
-    return r < BK ? r * ROWB + ((ch ^ fK(r)) * 16) : HALFB + (r - BK) * ROWB + ((ch ^ fV(r - BK)) * 16);
-  };
 
   // Workgroup ids are dealt round-robin over the 8 XCDs; give every XCD a contiguous run of slices
   // so that workgroups sharing K/V rows (same prompt and KV head) share one L2.
@@ -101,40 +84,16 @@ __global__ __launch_bounds__(256, SP_OCC) void prefill_bf16_kernel(PlanDev pd, c
   const int slice_begin = pd.wg_begin[wg], slice_end = pd.wg_begin[wg + 1];
   if (slice_begin >= slice_end) return;
 
-  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31,
-            half = lane >> 5;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
   const int G = pd.n_q_heads / pd.n_kv_heads;
+  const int tr_row = (lane & 15) >> 2;                          // transpose-read source: key row within 4
+  const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);   // and first of 4 dims within 32
   const float scale2 = scale * kLog2e;
-  const uint32_t ring_base = (uint32_t)(size_t)(lds_byte *)ring;
+  const int lrow = tid / CPR, lcol = (tid % CPR) * 8;           // this thread's row / column in a load pass
 
-  // DMA geometry of this lane: the wave fills stage rows [16*wave, 16*wave + 16), RG rows per
-  // instruction; the lane writes slot position (lane % CPR) of row (lane / CPR) of that group and
-  // therefore fetches the chunk that the swizzle maps there.
-  const int drow = lane / CPR, dslot = lane % CPR;
-  const bool dma_is_v = WROWS * wave >= BK;                 // this wave's rows lie in the V half
+  u32x4 areg[LOADS], breg[LOADS];
+  float preg = 0.f;
 
-  // K-fragment read: row l32 (+32*sub), chunks 2j + half  ->  ((2j) ^ (f & ~1)) | ((half ^ f) & 1)
-  const int kf_f = fK(l32), kf_lo = (half ^ kf_f) & 1, kf_fh = kf_f & ~1;
-  // V transpose read: source lane s of a 16-lane group reads key row s/4, dims 4*(s%4)..+3 of a
-  // 16-dim block; lane i receives dim i of the 4 keys.
-  const int tr_row = (lane & 15) >> 2;
-  const int tr_chlo = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1), tr_sub8 = (lane & 1) * 8;
-  const int tr_f = fV(4 * half + tr_row);                  // rows differ from this by multiples of 8
-
-  // stage ids of an item: -2 = Q tile rows 0..63, -1 = Q tile rows 64..127 (skipped when the
-  // tile has no such rows), 0 .. n-1 = K/V stages
-  auto n_stages = [](const WorkItem &w) { return (w.anc_keys + w.row0 + w.n_rows + BK - 1) / BK; };
-  auto has_q1 = [](const WorkItem &w) { return 32 * (2 / HPW) < w.n_rows; };
-  auto fetch_item = [&](int local) -> WorkItem {          // local index inside the staged batch
-    const int4 a = *reinterpret_cast<const int4 *>(&s_items[local]);
-    const int4 b = *(reinterpret_cast<const int4 *>(&s_items[local]) + 1);
-    WorkItem w;
-    w.tok_start = __builtin_amdgcn_readfirstlane(a.x); w.row0 = __builtin_amdgcn_readfirstlane(a.y);
-    w.n_rows = __builtin_amdgcn_readfirstlane(a.z); w.anc_keys = __builtin_amdgcn_readfirstlane(a.w);
-    w.range_off = __builtin_amdgcn_readfirstlane(b.x); w.n_ranges = __builtin_amdgcn_readfirstlane(b.y);
-    w.head0 = __builtin_amdgcn_readfirstlane(b.z); w.r0_start = __builtin_amdgcn_readfirstlane(b.w);
-    return w;
-  };
   // virtual key -> packed token for item w
   auto map_tok = [&](const WorkItem &w, int vk) -> int {
     vk = min(vk, w.anc_keys + w.row0 + w.n_rows - 1);           // past the end: re-read the last key (masked)
@@ -148,93 +107,98 @@ __global__ __launch_bounds__(256, SP_OCC) void prefill_bf16_kernel(PlanDev pd, c
     }
     return tok;
   };
-  // issue this wave's NDMA loads of stage st of item w into ring slot `slot`
-  auto issue = [&](const WorkItem &w, int st, int slot) {
-    const uint32_t lds0 = ring_base + slot * STAGEB + WROWS * wave * ROWB;   // the wave's rows are contiguous
+  // issue the global loads of stage st of item w (st = -1: the Q tile)
+  auto gload = [&](const WorkItem &w, int st) {
+    if (st < 0) {
 #pragma unroll
-    for (int m = 0; m < NDMA; ++m) {
-      const int r = WROWS * wave + RG * m + drow;               // stage row filled by this lane
-      const int rh = dma_is_v ? r - BK : r;                     // row inside its half
-      const int ch = dslot ^ (dma_is_v ? fV(rh) : fK(rh));      // chunk that belongs at this position
-      const __bf16 *src;
-      if (st < 0) {
-        const int tr = 64 * (st + 2) + r;                       // tile row; its 32-row slot = (token block, head)
-        const int sl = tr >> 5;
-        const int tok = w.tok_start + w.row0 + min(32 * (sl / HPW) + (tr & 31), w.n_rows - 1);
-        src = Q + ((uint64_t)(uint32_t)tok * q_ts + (uint32_t)(w.head0 + sl % HPW) * q_hs + ch * 8);
-      } else {
-        const int tok = map_tok(w, st * BK + rh);
-        src = (dma_is_v ? V : K) + ((uint64_t)(uint32_t)tok * kv_ts + (uint32_t)(w.head0 / G) * kv_hs + ch * 8);
+      for (int m = 0; m < LOADS; ++m) {
+        const int r = lrow + m * RPP;                           // Q-tile rows r and BK + r
+        const int s0 = r >> 5, s1 = (BK + r) >> 5;              // their 32-row slots
+        const int t0 = w.tok_start + w.row0 + min(32 * (s0 / HPW) + (r & 31), w.n_rows - 1);
+        const int t1 = w.tok_start + w.row0 + min(32 * (s1 / HPW) + ((BK + r) & 31), w.n_rows - 1);
+        areg[m] = ld16(Q + ((uint64_t)(uint32_t)t0 * q_ts + (uint32_t)(w.head0 + s0 % HPW) * q_hs + lcol));
+        breg[m] = ld16(Q + ((uint64_t)(uint32_t)t1 * q_ts + (uint32_t)(w.head0 + s1 % HPW) * q_hs + lcol));
       }
-      dma16(src, lds0 + m * (RG * ROWB));
+    } else {
+      const uint32_t hoff = (uint32_t)(w.head0 / G) * kv_hs + lcol;
+#pragma unroll
+      for (int m = 0; m < LOADS; ++m) {
+        const uint64_t off = (uint64_t)(uint32_t)map_tok(w, st * BK + lrow + m * RPP) * kv_ts + hoff;
+        areg[m] = ld16(K + off);
+        breg[m] = ld16(V + off);
+      }
+      if (BIAS && tid < BK) preg = pd.tok_pos[map_tok(w, st * BK + tid)];
     }
   };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int m = 0; m < LOADS; ++m) {
+      st16(&stK[buf][lrow + m * RPP][lcol], areg[m]);
+      st16(&stV[buf][lrow + m * RPP][lcol], breg[m]);
+    }
+    if (BIAS && tid < BK) Ps[buf][tid] = preg;
+  };
+
+  // Work items are read from an LDS copy of the slice (no pointer chasing in the stream loop).
+  auto fetch_item = [&](int local) -> WorkItem {          // local index inside the staged batch
+    const int4 a = *reinterpret_cast<const int4 *>(&s_items[local]);
+    const int4 b = *(reinterpret_cast<const int4 *>(&s_items[local]) + 1);
+    WorkItem w;
+    w.tok_start = __builtin_amdgcn_readfirstlane(a.x); w.row0 = __builtin_amdgcn_readfirstlane(a.y);
+    w.n_rows = __builtin_amdgcn_readfirstlane(a.z); w.anc_keys = __builtin_amdgcn_readfirstlane(a.w);
+    w.range_off = __builtin_amdgcn_readfirstlane(b.x); w.n_ranges = __builtin_amdgcn_readfirstlane(b.y);
+    w.head0 = __builtin_amdgcn_readfirstlane(b.z); w.r0_start = __builtin_amdgcn_readfirstlane(b.w);
+    return w;
+  };
+  auto n_stages = [](const WorkItem &w) { return (w.anc_keys + w.row0 + w.n_rows + BK - 1) / BK; };
 
   bf16x8 qf[NJ];
   f32x16 o[NC];
   float m_run = kNegBig, l_run = 0.f, slope2 = 0.f, pos_q = 0.f;
-  // geometry of the item whose accumulators are live (set at its Q stage)
-  int head = 0, r0 = 0, my_limit = 0, wave_last = 0, wave_first_limit = 0;
-  bool active = false;
 
-  // normalise and store the live accumulators of item w.  `slot` is a ring slot nobody reads any
-  // more and whose rows [16*wave, +16) this wave itself refills next, so they are private to it:
-  // O^T (one query row per lane) is transposed through them, 16 rows at a time, so that the global
-  // stores are whole 16-byte chunks of contiguous rows.
-  auto epilogue = [&](const WorkItem &w, int slot) {
-    if (!active) return;
-    const float inv = 1.f / xhalf_sum(l_run);
-    int zero;                                              // opaque 0: keeps the address arithmetic of the
-    asm volatile("v_mov_b32 %0, 0" : "=v"(zero));          // epilogue out of the registers of the stream loop
-    unsigned char *sl = ring + slot * STAGEB + zero;
-    const int rows_here = min(32, w.n_rows - r0);
-    __bf16 *ob = O + ((uint64_t)(uint32_t)(w.tok_start + w.row0 + r0) * q_ts + (uint32_t)head * q_hs);
-#pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-      if ((l32 >> 4) == pass) {
-        const int r = WROWS * wave + ((l32 + zero) & 15);
-#pragma unroll
-        for (int c = 0; c < NC; ++c)
-#pragma unroll
-          for (int q4 = 0; q4 < 4; ++q4) {
-            bf16x4 w4;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) w4[e] = static_cast<__bf16>(o[c][4 * q4 + e] * inv);
-            *reinterpret_cast<bf16x4 *>(sl + row_chunk(r, 4 * c + q4) + 8 * half) = w4;
-          }
-      }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-      for (int i = 0; i < 16 * CPR / 64; ++i) {
-        const int id = lane + zero + 64 * i, row = id / CPR, ch = id % CPR;
-        const u32x4 v = *reinterpret_cast<const u32x4 *>(sl + row_chunk(WROWS * wave + row, ch));
-        if (16 * pass + row < rows_here && !(dbg & 4))
-          st16(ob + ((uint64_t)(uint32_t)(16 * pass + row) * q_ts + ch * 8), v);
-      }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-    }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // LDS reads done before this wave's DMA refills
-  };
+  for (int batch = slice_begin; batch < slice_end; batch += kItemBatch) {
+    int it = batch;
+    const int it_end = min(batch + kItemBatch, slice_end);
+    __syncthreads();                                     // previous batch fully consumed
+    for (int i = tid; i < (it_end - it) * 2; i += T)
+      reinterpret_cast<int4 *>(s_items)[i] = reinterpret_cast<const int4 *>(pd.items + it)[i];
+    __syncthreads();
+    WorkItem cur = fetch_item(0);
+    WorkItem nxt = cur;
+    if (it + 1 < it_end) nxt = fetch_item(1);
+    int st = -1;                       // current stage of the current item
+    int buf = 0;
 
-  // everything a wave does for stage st of item w, resident in ring slot `slot`
-  auto compute = [&](const WorkItem &w, int st, int slot, int it_parity) {
-    const unsigned char *sl = ring + slot * STAGEB;
-    if (st < 0) {
-      // Q stages.  The 32-row block owned by a wave rotates with the item index so that the long
+    gload(cur, -1);
+    sstore(0);
+    __syncthreads();
+
+    while (true) {
+      // which stage follows?  (K/V stage of this item, or the Q tile of the next item)
+      const bool last_stage = st + 1 >= n_stages(cur);
+      const bool have_next = !last_stage || it + 1 < it_end;
+      if (have_next) {
+        if (!last_stage) gload(cur, st + 1);
+        else gload(nxt, -1);
+      }
+
+      // The 32-row block owned by this wave rotates with the item index so that the long
       // (late-row) blocks of the resident workgroups do not pile up on one SIMD.
-      const int qs = (wave + it_parity) % NW;               // tile slot (token block, head) of this wave
-      if (st == -2) {                                       // new item: geometry and fresh accumulators
-        head = w.head0 + qs % HPW;
-        r0 = 32 * (qs / HPW);
-        active = r0 < w.n_rows;
-        const int base = w.anc_keys + w.row0;               // virtual key of tile row 0 = its diagonal
-        const int my_row = min(r0 + l32, w.n_rows - 1);     // clamped: padded lanes repeat the last row
-        my_limit = base + my_row;
-        wave_last = base + min(r0 + 31, w.n_rows - 1);
-        wave_first_limit = base + r0;
+      const int slot = (wave + it) % NW;
+      const int head = cur.head0 + slot % HPW;
+      const int r0 = 32 * (slot / HPW);                     // first tile row of this wave
+      const bool active = r0 < cur.n_rows;
+      const int base = cur.anc_keys + cur.row0;             // virtual key of tile row 0 = its diagonal
+      const int my_row = min(r0 + l32, cur.n_rows - 1);     // clamped: padded lanes repeat the last row
+      const int my_limit = base + my_row;                   // last visible virtual key of this lane's row
+      const int wave_last = base + min(r0 + 31, cur.n_rows - 1);
+      const int wave_first_limit = base + r0;
+
+      if (st < 0) {
+        // Q stage: pull this wave's Q fragment (B operand; k-slot block j covers dims [16j + 8*half, +8))
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+          qf[j] = *reinterpret_cast<const bf16x8 *>(srow(buf, 32 * slot + l32) + 16 * j + 8 * half);
 #pragma unroll
         for (int c = 0; c < NC; ++c)
 #pragma unroll
@@ -243,174 +207,147 @@ __global__ __launch_bounds__(256, SP_OCC) void prefill_bf16_kernel(PlanDev pd, c
         l_run = 0.f;
         if (BIAS) {
           slope2 = pd.slopes[head] * kLog2e;
-          pos_q = pd.tok_pos[w.tok_start + w.row0 + my_row];
+          pos_q = pd.tok_pos[cur.tok_start + cur.row0 + my_row];
         }
-      }
-      if ((qs >> 1) == st + 2) {
-        // this wave's Q rows are in the stage: B operand of S^T = K Q^T, k-slot block j covers
-        // dims [16j + 8*half, +8)
-#pragma unroll
-        for (int j = 0; j < NJ; ++j)
-          qf[j] = *reinterpret_cast<const bf16x8 *>(sl + row_chunk(32 * (qs & 1) + l32, 2 * j + half));
-      }
-      return;
-    }
-    {
-      constexpr int sub = 0;
-      const int vk0 = st * BK;
-      if (!active || vk0 > wave_last || (dbg & 1)) return;   // block entirely above this wave's diagonal
-
-      f32x16 s;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s[i] = 0.f;
-      const unsigned char *krow = sl + (32 * sub + l32) * ROWB;
-#pragma unroll
-      for (int j = 0; j < NJ; ++j) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(krow + ((((2 * j) ^ kf_fh) | kf_lo) * 16));
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[j], s, 0, 0, 0);
-      }
-
-      // scores in log2 units: t = s * scale2 (+ bias); masked entries -> -inf
-      if (BIAS) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-          s[i] = fmaf(s[i], scale2, slope2 * (Ps[slot][32 * sub + 8 * (i / 4) + 4 * half + (i % 4)] - pos_q));
-      }
-      if (vk0 + 31 > wave_first_limit) {                   // diagonal block: some rows see only part of it
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-          if (vk0 + 8 * (i / 4) + 4 * half + (i % 4) > my_limit) s[i] = -INFINITY;
-      }
-      float mx = fmaxf(s[0], s[1]);
-#pragma unroll
-      for (int i = 2; i < 16; ++i) mx = fmaxf(mx, s[i]);
-      if (!BIAS) mx *= scale2;                             // scale2 > 0: max commutes with the scaling
-      mx = xhalf_max(mx);
-      // The reference maximum is allowed to lag by up to 8 (factor 256 in p), which fp32 sums and
-      // bf16 P absorb; the accumulator registers are rescaled only when some row exceeds that.
-      if (__any(mx > m_run + 8.f)) {
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = fast_exp2(m_run - m_new);
-        m_run = m_new;
-        l_run *= alpha;
-#pragma unroll
-        for (int c = 0; c < NC; ++c)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) o[c][i] *= alpha;
-      }
-      float ls = 0.f;
-      bf16x8 pb[2];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float p = BIAS ? fast_exp2(s[i] - m_run) : fast_exp2(fmaf(s[i], scale2, -m_run));
-        ls += p;
-        pb[i / 8][i % 8] = static_cast<__bf16>(p);
-      }
-      l_run += ls;
-      const unsigned char *vrow = sl + HALFB + (32 * sub + 4 * half + tr_row) * ROWB + tr_sub8;
-#pragma unroll
-      for (int c = 0; c < NC; ++c) {
-        const int choff = (((4 * c) ^ tr_f) + tr_chlo) * 16;
-#pragma unroll
-        for (int mm = 0; mm < 2; ++mm) {
-          const unsigned char *vp = vrow + 16 * mm * ROWB + choff;
-          const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)vp);
-          const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(vp + 8 * ROWB));
-          const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[mm], o[c], 0, 0, 0);
-        }
-      }
-    }
-  };
-
-  for (int batch = slice_begin; batch < slice_end; batch += kItemBatch) {
-    const int n_local = min(kItemBatch, slice_end - batch);
-    __syncthreads();                                     // previous batch fully consumed
-    for (int i = tid; i < n_local * 2; i += T)
-      reinterpret_cast<int4 *>(s_items)[i] = reinterpret_cast<const int4 *>(pd.items + batch)[i];
-    __syncthreads();
-
-    // cursors: c = stage being computed (ring slot c_slot), l = next stage to issue (two ahead)
-    int c_it = 0, c_st = -2, l_it = 0, l_st = -2, c_slot = 0, l_slot = 0;
-    WorkItem cw = fetch_item(0), lw = cw, pw = cw;         // pw: item whose epilogue is pending
-    bool pending = false;
-    auto advance = [&](int &it, int &st, WorkItem &w) {
-      if (st == -2) st = has_q1(w) ? -1 : 0;
-      else if (st + 1 < n_stages(w)) st += 1;
-      else {
-        it += 1;
-        st = -2;
-        if (it < n_local) w = fetch_item(it);
-      }
-    };
-    auto issue_next = [&]() {                              // issue the stage at the load cursor, advance it
-      if (l_it < n_local) {
-        if (!(dbg & 2)) issue(lw, l_st, l_slot);
-        if (BIAS && l_st >= 0 && tid < BK) Ps[l_slot][tid] = pd.tok_pos[map_tok(lw, l_st * BK + tid)];
-        advance(l_it, l_st, lw);
-        l_slot = l_slot + 1 == NS ? 0 : l_slot + 1;
-      }
-    };
-    issue_next();
-    issue_next();                                          // every item has at least two stages
-
-    while (true) {
-      // Wait for the stage at the compute cursor.  This wave has issued that stage and possibly
-      // one younger one: all but the youngest stage's loads must have landed (all of them when
-      // nothing younger is in flight); then meet the other waves.
-      const int ahead = l_slot - c_slot + (l_slot < c_slot ? NS : 0);   // stages issued, not computed: 1 or 2
-      if (ahead == 2) {
-        if (NDMA == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
       } else {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int sub = 0; sub < BK / 32; ++sub) {
+          const int vk0 = st * BK + 32 * sub;
+          if (!active || vk0 > wave_last) continue;           // block entirely above this wave's diagonal
+
+          f32x16 s;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s[i] = 0.f;
+#pragma unroll
+          for (int j = 0; j < NJ; ++j) {
+            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&stK[buf][32 * sub + l32][16 * j + 8 * half]);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[j], s, 0, 0, 0);
+          }
+
+          // scores in log2 units: t = s * scale2 (+ bias); masked entries -> -inf
+          if (BIAS) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+              s[i] = fmaf(s[i], scale2, slope2 * (Ps[buf][32 * sub + 8 * (i / 4) + 4 * half + (i % 4)] - pos_q));
+          }
+          if (vk0 + 31 > wave_first_limit) {                 // diagonal block: some rows see only part of it
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+              if (vk0 + 8 * (i / 4) + 4 * half + (i % 4) > my_limit) s[i] = -INFINITY;
+          }
+          float mx = fmaxf(s[0], s[1]);
+#pragma unroll
+          for (int i = 2; i < 16; ++i) mx = fmaxf(mx, s[i]);
+          if (!BIAS) mx *= scale2;                           // scale2 > 0: max commutes with the scaling
+          mx = xhalf_max(mx);
+          // The reference maximum is allowed to lag by up to 8 (factor 256 in p), which fp32 sums and
+          // bf16 P absorb; the accumulator registers are rescaled only when some row exceeds that.
+          if (__any(mx > m_run + 8.f)) {
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = fast_exp2(m_run - m_new);
+            m_run = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
+#pragma unroll
+              for (int i = 0; i < 16; ++i) o[c][i] *= alpha;
+          }
+          float ls = 0.f;
+          bf16x8 pb[2];
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const float p = BIAS ? fast_exp2(s[i] - m_run) : fast_exp2(fmaf(s[i], scale2, -m_run));
+            ls += p;
+            pb[i / 8][i % 8] = static_cast<__bf16>(p);
+          }
+          l_run += ls;
+#pragma unroll
+          for (int c = 0; c < NC; ++c) {
+#pragma unroll
+            for (int mm = 0; mm < 2; ++mm) {
+              // V^T fragment through the LDS transpose read: a 16-lane group hands in a 4-key x 16-dim
+              // block (lane s: key s/4, dims 4*(s%4)..+3) and lane i receives dim i of the 4 keys.
+              const __bf16 *vp = &stV[buf][32 * sub + 16 * mm + 4 * half + tr_row][32 * c + tr_col];
+              const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)vp);
+              const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(vp + 8 * LDV));
+              const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+              o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[mm], o[c], 0, 0, 0);
+            }
+          }
+        }
+
+        if (last_stage) {
+          // Epilogue of the item.  O^T sits in registers one query row per lane; it is transposed
+          // through this wave's 32-row slice of the (now dead) K/V stage so that the global stores
+          // are whole 16-byte chunks of contiguous rows.
+          __syncthreads();                                   // every wave is done reading this stage
+          if (active) {
+            const float inv = 1.f / xhalf_sum(l_run);
+            __bf16 *orow = srow(buf, 32 * wave + l32) + 4 * half;
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
+#pragma unroll
+              for (int q4 = 0; q4 < 4; ++q4) {
+                bf16x4 w4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w4[e] = static_cast<__bf16>(o[c][4 * q4 + e] * inv);
+                *reinterpret_cast<bf16x4 *>(orow + 32 * c + 8 * q4) = w4;
+              }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const int rows_here = min(32, cur.n_rows - r0);
+            __bf16 *ob = O + ((uint64_t)(uint32_t)(cur.tok_start + cur.row0 + r0) * q_ts + (uint32_t)head * q_hs);
+#pragma unroll
+            for (int i = 0; i < 32 * CPR / 64; ++i) {
+              const int id = lane + 64 * i, row = id / CPR, ch = id % CPR;
+              if (row < rows_here)
+                st16(ob + ((uint64_t)(uint32_t)row * q_ts + ch * 8),
+                     *reinterpret_cast<const u32x4 *>(srow(buf, 32 * wave + row) + ch * 8));
+            }
+          }
+        }
       }
-      __builtin_amdgcn_s_barrier();
-      asm volatile("" ::: "memory");                       // no LDS access may move above the barrier
-      if (pending) {                                       // the previous step finished an item
-        epilogue(pw, c_slot == 0 ? NS - 1 : c_slot - 1);
-        pending = false;
+
+      if (!have_next) break;
+      sstore(buf ^ 1);
+      __syncthreads();
+      buf ^= 1;
+      if (!last_stage) {
+        ++st;
+      } else {
+        ++it;
+        cur = nxt;
+        if (it + 1 < it_end) nxt = fetch_item(it + 1 - batch);
+        st = -1;
       }
-      issue_next();
-      compute(cw, c_st, c_slot, c_it + batch);
-      if (c_st + 1 >= n_stages(cw)) { pw = cw; pending = true; }
-      advance(c_it, c_st, cw);
-      c_slot = c_slot + 1 == NS ? 0 : c_slot + 1;
-      if (c_it >= n_local) break;
     }
-    // drain: the last item's accumulators
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    epilogue(pw, c_slot == 0 ? NS - 1 : c_slot - 1);
   }
 }
 
-template <int D, int HPW>
+template <int D, int HPW, int NW>
 static hipError_t launch_hpw(const sp_plan *plan, const PrefillArgs &a, hipStream_t s) {
   const dim3 grid(unsigned(plan->dev.n_wg));
-  const char *e = getenv("SP_DBG");
-  const int dbg = e ? atoi(e) : 0;
   const __bf16 *Q = static_cast<const __bf16 *>(a.Q), *K = static_cast<const __bf16 *>(a.K),
                *V = static_cast<const __bf16 *>(a.V);
   __bf16 *O = static_cast<__bf16 *>(a.O);
   const uint32_t qts = uint32_t(a.q_tok_stride), qhs = uint32_t(a.q_head_stride), kts = uint32_t(a.kv_tok_stride),
                  khs = uint32_t(a.kv_head_stride);
   if (plan->has_slopes)
-    hipLaunchKernelGGL((prefill_bf16_kernel<D, HPW, true>), grid, dim3(256), 0, s, plan->dev, Q, K, V, O,
-                       qts, qhs, kts, khs, a.scale, dbg);
+    hipLaunchKernelGGL((prefill_bf16_kernel<D, HPW, NW, true>), grid, dim3(64 * NW), 0, s, plan->dev, Q, K, V, O,
+                       qts, qhs, kts, khs, a.scale);
   else
-    hipLaunchKernelGGL((prefill_bf16_kernel<D, HPW, false>), grid, dim3(256), 0, s, plan->dev, Q, K, V, O,
-                       qts, qhs, kts, khs, a.scale, dbg);
+    hipLaunchKernelGGL((prefill_bf16_kernel<D, HPW, NW, false>), grid, dim3(64 * NW), 0, s, plan->dev, Q, K, V, O,
+                       qts, qhs, kts, khs, a.scale);
   return hipGetLastError();
 }
 
 template <int D>
 static hipError_t launch_d(const sp_plan *plan, const PrefillArgs &a, hipStream_t s) {
   switch (plan->heads_per_wg) {
-    case 4: return launch_hpw<D, 4>(plan, a, s);
-    case 2: return launch_hpw<D, 2>(plan, a, s);
-    default: return launch_hpw<D, 1>(plan, a, s);
+    case 4: return launch_hpw<D, 4, 4>(plan, a, s);
+    case 2: return launch_hpw<D, 2, 2>(plan, a, s);
+    default: return launch_hpw<D, 1, 2>(plan, a, s);
   }
 }
 
