@@ -133,6 +133,9 @@ def main():
     ap.add_argument("--workload", default="c2_mha7b_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode-c5", action="store_true")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="short run for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE: a plain elementwise kernel of known "
+                         "traffic (calibration), then a few steps; prints no benchmark line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (one process, one MI355X); --gpus %d is not "
@@ -173,6 +176,18 @@ def main():
                                  d["dk"][s], d["dv"][s], d["o"], scale, resp_len_add=s)
         if ev: ev[4].record()
 
+    if args.traffic_probe:
+        # calibration: y = x + 1 over 1 GiB of bf16 reads 2^30 bytes and writes 2^30 bytes
+        x = torch.zeros(1 << 29, dtype=torch.bfloat16, device="cuda")
+        y = torch.empty_like(x)
+        for _ in range(3):
+            torch.add(x, 1, out=y)
+        for i in range(max(args.steps, 2)):
+            step(i)
+        _bench_decode_c5(ctx, torch, B, steps=8, reps=1)
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_probe": True, "calibration_kernel": "torch.add bf16, 2^30 B read + 2^30 B written"}))
+        return
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -229,7 +244,9 @@ def main():
     tr = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tr):
         try:
-            out["roofline"]["traffic"] = json.load(open(tr)).get("prefill_bf16_kernel:" + wl.name)
+            tj = json.load(open(tr))
+            out["roofline"]["traffic"] = tj.get("prefill_bf16_kernel:" + wl.name)
+            out["saliency"]["traffic"] = tj.get("row_loglik_kernel:" + wl.name)
         except Exception:
             pass
 
@@ -240,12 +257,12 @@ def main():
     print(json.dumps(out))
 
 
-def _bench_decode_c5(ctx, torch, B):
+def _bench_decode_c5(ctx, torch, B, steps=None, reps=5):
     """Long pruned decode: 64 prompts, 2 of 20 paths kept, 256 steps over the growing cache."""
     wl = sp_synth.WORKLOADS["c5_decode_bf16"]
     st = sp_synth.forkjoin_segtable(wl.preamble_len, [[wl.doc_len] * wl.n_paths] * wl.n_prompts, wl.query_len)
     g = torch.Generator(device="cuda"); g.manual_seed(wl.seed)
-    H, d, S, Bn = wl.n_kv_heads, wl.head_dim, wl.decode_steps, wl.n_prompts
+    H, d, S, Bn = wl.n_kv_heads, wl.head_dim, (steps or wl.decode_steps), wl.n_prompts
     rn = lambda *s: torch.randn(s, generator=g, device="cuda").to(torch.bfloat16)
     K, V = rn(st.n_tokens, H, d), rn(st.n_tokens, H, d)
     dq, dk, dv = rn(S, Bn, H, d), rn(S, Bn, H, d), rn(S, Bn, H, d)
@@ -264,7 +281,7 @@ def _bench_decode_c5(ctx, torch, B):
     loop()
     torch.cuda.synchronize()
     times = []
-    for _ in range(5):
+    for _ in range(reps):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(); loop(); e1.record()
         torch.cuda.synchronize()

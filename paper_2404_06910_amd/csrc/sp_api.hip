@@ -272,8 +272,12 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
         }
     }
   }
-  // Persistent workgroups: two per compute unit, each owning a contiguous, cost-balanced slice of
-  // the work list (cost = LDS stages streamed: one for Q plus the K/V stages, plus the epilogue).
+  // Persistent workgroups, 8 waves per compute unit.  The work list is cut into 8 contiguous,
+  // cost-balanced ranges, one per XCD (cost = LDS stages streamed: one for Q plus the K/V stages,
+  // plus the epilogue); inside a range the items are dealt round-robin to that XCD's workgroups.
+  // At any moment an XCD therefore works on a window of consecutive items -- all tiles of a path
+  // and the paths of one (prompt, KV head) -- so that every K/V row is fetched from HBM once and
+  // then found in that XCD's L2 by the other tiles that need it.
   {
     int n_cu = 256;
     if (ctx) {
@@ -282,17 +286,17 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
         n_cu = prop.multiProcessorCount;
     }
     const int32_t stage_keys = 16 * p->waves_per_wg;
-    const int32_t n_wg = (((8 / p->waves_per_wg) * n_cu + 7) / 8) * 8;   // 8 waves per compute unit
+    p->n_wg = (((8 / p->waves_per_wg) * n_cu + 7) / 8) * 8;
     int64_t total = 0;
     auto stages = [&](const sp::WorkItem &w) { return (w.anc_keys + w.row0 + w.n_rows + stage_keys - 1) / stage_keys; };
     for (auto &w : p->items) total += 2 + stages(w);
-    p->wg_begin.assign(n_wg + 1, static_cast<int32_t>(p->items.size()));
+    p->wg_begin.assign(9, static_cast<int32_t>(p->items.size()));
     p->wg_begin[0] = 0;
     int64_t acc = 0;
     int32_t c = 1;
-    for (size_t i = 0; i < p->items.size() && c < n_wg; ++i) {
+    for (size_t i = 0; i < p->items.size() && c < 8; ++i) {
       acc += 2 + stages(p->items[i]);
-      while (c < n_wg && acc * n_wg >= total * c) p->wg_begin[c++] = static_cast<int32_t>(i + 1);
+      while (c < 8 && acc * 8 >= total * c) p->wg_begin[c++] = static_cast<int32_t>(i + 1);
     }
   }
 
@@ -382,7 +386,7 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
     d.dec_ranges = reinterpret_cast<const sp::KeyRange *>(base + o_dr);
     d.n_items = static_cast<int32_t>(p->items.size());
     d.wg_begin = reinterpret_cast<const int32_t *>(base + o_wgb);
-    d.n_wg = static_cast<int32_t>(p->wg_begin.size()) - 1;
+    d.n_wg = p->n_wg;
     d.n_tokens = p->n_tokens;
     d.n_prompts = p->n_prompts;
     d.n_q_heads = n_q_heads; d.n_kv_heads = n_kv_heads; d.head_dim = head_dim;

@@ -114,37 +114,43 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(PlanDev pd, DecodeD
     for (int e = 0; e < EV; ++e) acc[c][e] = 0.f;
   }
 
-  for (int vk0 = kg; vk0 < n_total; vk0 += KPW * kDecUnroll) {
+  // One batch = kDecUnroll keys per lane group.  Batches are software-pipelined: the loads of the
+  // next batch are issued before the arithmetic of the current one (two register sets).
+  struct Batch {
     u32x4 kraw[kDecUnroll], vraw[kDecUnroll];
     float pk[kDecUnroll];
     bool ok[kDecUnroll];
+  };
+  auto load_batch = [&](int vk0, Batch &bt) {
 #pragma unroll
     for (int u = 0; u < kDecUnroll; ++u) {
       const int vk = vk0 + u * KPW;
-      ok[u] = vk < n_total;
+      bt.ok[u] = vk < n_total;
       const T *kptr = kn, *vptr = vn;        // also the in-bounds stand-in for lanes past the end
-      pk[u] = pos_q;
+      bt.pk[u] = pos_q;
       if (vk < n_pref) {
         int i = 0;
         while (i + 1 < nr && r_cum[i + 1] <= vk) ++i;
         const int64_t tok = r_start[i] + (vk - r_cum[i]);
         kptr = Kp + tok * a.kv_tok_stride;
         vptr = Vp + tok * a.kv_tok_stride;
-        if (bias) pk[u] = pd.tok_pos[tok];
+        if (bias) bt.pk[u] = pd.tok_pos[tok];
       } else if (vk < n_pref + len_r) {
         const int64_t row = vk - n_pref;
         kptr = Kr + row * resp_row;
         vptr = Vr + row * resp_row;
-        if (bias) pk[u] = a.pos_resp[(int64_t)b * a.resp_capacity + row];
+        if (bias) bt.pk[u] = a.pos_resp[(int64_t)b * a.resp_capacity + row];
       }
-      kraw[u] = ld16(kptr);
-      vraw[u] = ld16(vptr);
+      bt.kraw[u] = ld16(kptr);
+      bt.vraw[u] = ld16(vptr);
     }
+  };
+  auto compute_batch = [&](const Batch &bt) {
     float t[kDecUnroll][GC];
 #pragma unroll
     for (int u = 0; u < kDecUnroll; ++u) {
       float kf[EV];
-      Elem<T>::unpack(kraw[u], kf);
+      Elem<T>::unpack(bt.kraw[u], kf);
 #pragma unroll
       for (int c = 0; c < GC; ++c) {
         float d = 0.f;
@@ -153,7 +159,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(PlanDev pd, DecodeD
 #pragma unroll
         for (int off = LPK / 2; off >= 1; off >>= 1) d += __shfl_xor(d, off);
         // distance penalty -slope * (pos_q - pos_k), in log2 units
-        t[u][c] = ok[u] ? d - slope2[c] * (pos_q - pk[u]) : -INFINITY;
+        t[u][c] = bt.ok[u] ? d - slope2[c] * (pos_q - bt.pk[u]) : -INFINITY;
       }
     }
 #pragma unroll
@@ -171,7 +177,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(PlanDev pd, DecodeD
 #pragma unroll
     for (int u = 0; u < kDecUnroll; ++u) {
       float vf[EV];
-      Elem<T>::unpack(vraw[u], vf);
+      Elem<T>::unpack(bt.vraw[u], vf);
 #pragma unroll
       for (int c = 0; c < GC; ++c) {
         const float p = fast_exp2(t[u][c] - m[c]);
@@ -179,6 +185,21 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(PlanDev pd, DecodeD
 #pragma unroll
         for (int e = 0; e < EV; ++e) acc[c][e] = fmaf(p, vf[e], acc[c][e]);
       }
+    }
+  };
+  {
+    constexpr int STEP = KPW * kDecUnroll;
+    Batch b0, b1;
+    int vk0 = kg;
+    if (vk0 < n_total) load_batch(vk0, b0);
+    while (vk0 < n_total) {
+      if (vk0 + STEP < n_total) load_batch(vk0 + STEP, b1);
+      compute_batch(b0);
+      vk0 += STEP;
+      if (vk0 >= n_total) break;
+      if (vk0 + STEP < n_total) load_batch(vk0 + STEP, b0);
+      compute_batch(b1);
+      vk0 += STEP;
     }
   }
 

@@ -49,7 +49,7 @@ struct PlanDev {
   const RowGroup *groups;
   const KeyRange *ranges;
   const WorkItem *items;
-  const int32_t *wg_begin;       // [n_wg+1] contiguous slice of the work list per persistent workgroup
+  const int32_t *wg_begin;       // [9] contiguous range of the work list per XCD
   const int32_t *tok_group;      // [n_tokens] row group of each token, -1 = uncovered
   const float *tok_pos;          // [n_tokens] or nullptr
   const float *slopes;           // [n_q_heads] or nullptr
@@ -86,6 +86,7 @@ struct sp_plan {
   int32_t waves_per_wg = 4;   // waves (32-row blocks) per prefill workgroup
   int32_t tile_rows = 0;      // token rows per prefill tile
   int32_t n_tiles = 0;
+  int32_t n_wg = 0;           // persistent prefill workgroups (a multiple of 8)
   int32_t max_ranges = 0;
   int32_t max_dec_ranges = 0; // largest joined-cache range count bound per prompt (shared + per-path max)
   int64_t visible_pairs = 0;

@@ -78,11 +78,13 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
   __shared__ float Ps[2][BK];
   __shared__ __attribute__((aligned(16))) WorkItem s_items[kItemBatch];
 
-  // Workgroup ids are dealt round-robin over the 8 XCDs; give every XCD a contiguous run of slices
-  // so that workgroups sharing K/V rows (same prompt and KV head) share one L2.
-  const int wg = (blockIdx.x % 8) * (pd.n_wg / 8) + blockIdx.x / 8;
-  const int slice_begin = pd.wg_begin[wg], slice_end = pd.wg_begin[wg + 1];
-  if (slice_begin >= slice_end) return;
+  // Workgroup ids are dealt round-robin over the 8 XCDs (id % 8).  Every XCD owns a contiguous range
+  // of the work list and deals its items round-robin to its workgroups, so the workgroups of an XCD
+  // work on a moving window of consecutive items and share their K/V rows through that XCD's L2.
+  const int xcd_wgs = pd.n_wg / 8, wg_in_xcd = blockIdx.x / 8;
+  const int x0 = pd.wg_begin[blockIdx.x % 8], x1 = pd.wg_begin[blockIdx.x % 8 + 1];
+  const int n_mine = (x1 - x0 - wg_in_xcd + xcd_wgs - 1) / xcd_wgs;   // items x0 + wg_in_xcd + k * xcd_wgs
+  if (x1 - x0 - wg_in_xcd <= 0) return;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
   const int G = pd.n_q_heads / pd.n_kv_heads;
@@ -156,12 +158,13 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
   f32x16 o[NC];
   float m_run = kNegBig, l_run = 0.f, slope2 = 0.f, pos_q = 0.f;
 
-  for (int batch = slice_begin; batch < slice_end; batch += kItemBatch) {
+  for (int batch = 0; batch < n_mine; batch += kItemBatch) {
     int it = batch;
-    const int it_end = min(batch + kItemBatch, slice_end);
+    const int it_end = min(batch + kItemBatch, n_mine);
     __syncthreads();                                     // previous batch fully consumed
     for (int i = tid; i < (it_end - it) * 2; i += T)
-      reinterpret_cast<int4 *>(s_items)[i] = reinterpret_cast<const int4 *>(pd.items + it)[i];
+      reinterpret_cast<int4 *>(s_items)[i] =
+          reinterpret_cast<const int4 *>(pd.items + (x0 + wg_in_xcd + (int64_t)(it + (i >> 1)) * xcd_wgs))[i & 1];
     __syncthreads();
     WorkItem cur = fetch_item(0);
     WorkItem nxt = cur;

@@ -97,21 +97,39 @@ __global__ __launch_bounds__(kSalThreads) void row_loglik_kernel(const T *__rest
   }
 }
 
-__global__ __launch_bounds__(256) void path_reduce_kernel(const float *__restrict__ lp,
-                                                          const int32_t *__restrict__ target,
-                                                          const int32_t *__restrict__ row_path, int64_t n_rows,
-                                                          const float *__restrict__ prior, int mode,
-                                                          float *__restrict__ score) {
+// Rows that are not scored carry lp = 0, so the SUM needs only row_path and lp; the MEAN also
+// counts the scored rows.  All loads of a thread are independent (issued together), partial sums
+// are combined in a fixed tree order.
+constexpr int kRedThreads = 1024;
+__global__ __launch_bounds__(kRedThreads) void path_reduce_kernel(const float *__restrict__ lp,
+                                                                  const int32_t *__restrict__ target,
+                                                                  const int32_t *__restrict__ row_path,
+                                                                  int64_t n_rows, const float *__restrict__ prior,
+                                                                  int mode, float *__restrict__ score) {
   const int slot = blockIdx.x;
   float acc = 0.f;
   int cnt = 0;
-  for (int64_t r = threadIdx.x; r < n_rows; r += 256)
-    if (row_path[r] == slot && target[r] >= 0) { acc += lp[r]; ++cnt; }
-  __shared__ float sa[256];
-  __shared__ int sc[256];
+  for (int64_t r0 = 0; r0 < n_rows; r0 += 4 * kRedThreads) {
+    int32_t rp[4];
+    float v[4];
+    int32_t tg[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t r = r0 + threadIdx.x + u * kRedThreads;
+      const bool in = r < n_rows;
+      rp[u] = in ? row_path[r] : -1;
+      v[u] = in ? lp[r] : 0.f;
+      tg[u] = (in && mode == 1) ? target[r] : 0;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (rp[u] == slot) { acc += v[u]; cnt += tg[u] >= 0 ? 1 : 0; }
+  }
+  __shared__ float sa[kRedThreads];
+  __shared__ int sc[kRedThreads];
   sa[threadIdx.x] = acc; sc[threadIdx.x] = cnt;
   __syncthreads();
-  for (int off = 128; off >= 1; off >>= 1) {
+  for (int off = kRedThreads / 2; off >= 1; off >>= 1) {
     if (threadIdx.x < off) { sa[threadIdx.x] += sa[threadIdx.x + off]; sc[threadIdx.x] += sc[threadIdx.x + off]; }
     __syncthreads();
   }
@@ -136,7 +154,7 @@ hipError_t launch_saliency(const void *logits, sp_dtype dt, int64_t n_rows, int6
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(path_reduce_kernel, dim3(n_slots), dim3(256), 0, s, lp_ws, target, row_path, n_rows, prior,
+  hipLaunchKernelGGL(path_reduce_kernel, dim3(n_slots), dim3(kRedThreads), 0, s, lp_ws, target, row_path, n_rows, prior,
                      mode, score);
   return hipGetLastError();
 }
