@@ -70,6 +70,9 @@ typedef struct {
   const float *tok_pos;          /* [n_tokens] real-valued positions (Sec. 3.2.2); may be NULL
                                     when alibi_slopes is NULL                                */
   const float *alibi_slopes;     /* [n_q_heads] linear distance-penalty slopes; NULL = none  */
+  const uint8_t *seg_cached;     /* [n_segments] nonzero: the segment's K/V come from a path cache
+                                    (Sec. 3.3.1, Alg. 2): its tokens serve as keys only and no
+                                    output rows are produced for them; NULL = nothing cached     */
 } sp_segtable;
 
 /* ---- context ------------------------------------------------------------------------- */
@@ -97,7 +100,8 @@ void sp_plan_destroy(sp_plan *plan);
  * segments fused for the query side) [5]=n_tiles [6]=n_work_items [7]=max ancestor ranges.
  * HOST out pointer. */
 sp_status sp_plan_info(const sp_plan *plan, int64_t info[8]);
-/* Visible (query token, key token) pairs per head, the unit of the prefill FLOP count
+/* Visible (query token, key token) pairs per head over the rows that are computed (tokens of
+ * cached segments are keys only), the unit of the prefill FLOP count
  * 4 * head_dim * n_q_heads * pairs. */
 int64_t sp_plan_visible_pairs(const sp_plan *plan);
 /* HOST out [n_prompts+1]: CSR of global path slots (slot = path_off[prompt] + path id). */
@@ -121,7 +125,8 @@ int64_t sp_plan_joined_keys(const sp_plan *plan, int32_t prompt, const int32_t *
  * over the tokens s visible to t.  One launch covers all prompts, paths and heads.
  * Q, O: DEVICE [n_tokens, n_q_heads, head_dim]; K, V: DEVICE [n_tokens, n_kv_heads, head_dim];
  * element strides given explicitly (innermost stride 1); dtype as in the plan; O must not
- * alias an input; rows of tokens not covered by any segment are left untouched.
+ * alias an input; rows of tokens not covered by any segment, and rows of segments flagged
+ * seg_cached, are left untouched.
  */
 sp_status sp_forkjoin_prefill(sp_ctx *ctx, const sp_plan *plan, const void *Q, const void *K, const void *V,
                               void *O, int64_t q_tok_stride, int64_t q_head_stride, int64_t kv_tok_stride,

@@ -32,7 +32,7 @@ class _SegTable(C.Structure):
     _fields_ = [("n_prompts", C.c_int32), ("n_segments", C.c_int32), ("n_tokens", C.c_int32),
                 ("prompt_seg_off", C.c_void_p), ("seg_tok_start", C.c_void_p), ("seg_tok_len", C.c_void_p),
                 ("seg_parent", C.c_void_p), ("seg_path", C.c_void_p), ("tok_pos", C.c_void_p),
-                ("alibi_slopes", C.c_void_p)]
+                ("alibi_slopes", C.c_void_p), ("seg_cached", C.c_void_p)]
 
 
 def lib() -> C.CDLL:
@@ -85,13 +85,15 @@ def _np_ptr(a: Optional[np.ndarray]):
 
 
 def _make_table(prompt_seg_off, seg_tok_start, seg_tok_len, seg_parent, seg_path, n_tokens, tok_pos=None,
-                alibi_slopes=None):
+                alibi_slopes=None, seg_cached=None):
     keep = [_i32(prompt_seg_off), _i32(seg_tok_start), _i32(seg_tok_len), _i32(seg_parent), _i32(seg_path)]
     pos = None if tok_pos is None else np.ascontiguousarray(np.asarray(tok_pos, dtype=np.float32))
     slopes = None if alibi_slopes is None else np.ascontiguousarray(np.asarray(alibi_slopes, dtype=np.float32))
+    cached = None if seg_cached is None else np.ascontiguousarray(np.asarray(seg_cached, dtype=np.uint8))
     t = _SegTable(len(keep[0]) - 1, len(keep[1]), int(n_tokens), _np_ptr(keep[0]), _np_ptr(keep[1]),
-                  _np_ptr(keep[2]), _np_ptr(keep[3]), _np_ptr(keep[4]), _np_ptr(pos), _np_ptr(slopes))
-    return t, keep + [pos, slopes]
+                  _np_ptr(keep[2]), _np_ptr(keep[3]), _np_ptr(keep[4]), _np_ptr(pos), _np_ptr(slopes),
+                  _np_ptr(cached))
+    return t, keep + [pos, slopes, cached]
 
 
 def _dev(t, what: str) -> int:
@@ -198,9 +200,9 @@ class Plan:
 
     def __init__(self, ctx: Optional[Context], prompt_seg_off, seg_tok_start, seg_tok_len, seg_parent, seg_path,
                  n_tokens: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dtype: int, tok_pos=None,
-                 alibi_slopes=None):
+                 alibi_slopes=None, seg_cached=None):
         t, keep = _make_table(prompt_seg_off, seg_tok_start, seg_tok_len, seg_parent, seg_path, n_tokens, tok_pos,
-                              alibi_slopes)
+                              alibi_slopes, seg_cached)
         self._h = C.c_void_p()
         self.ctx = ctx
         self.dtype = dtype

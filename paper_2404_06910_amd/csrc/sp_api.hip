@@ -194,6 +194,14 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
 
   // --- row groups: fuse a child that is packed right behind its parent into the parent's run
   std::vector<int32_t> group_of(S, -1), group_last;
+  auto is_cached = [&](int32_t s) { return t->seg_cached && t->seg_cached[s] != 0; };
+  // per row group: the row intervals [begin, end) that are computed (rows of cached segments are not)
+  std::vector<std::vector<std::pair<int32_t, int32_t>>> live_rows;
+  auto add_live = [&](int32_t g, int32_t begin, int32_t end) {
+    auto &v = live_rows[g];
+    if (!v.empty() && v.back().second == begin) v.back().second = end;
+    else v.push_back({begin, end});
+  };
   std::vector<int32_t> chain;
   for (int32_t b = 0; b < B; ++b) {
     for (int32_t s = t->prompt_seg_off[b]; s < t->prompt_seg_off[b + 1]; ++s) {
@@ -202,6 +210,7 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
         const int32_t g = group_of[par];
         if (group_last[g] == par && t->seg_tok_start[s] == t->seg_tok_start[par] + t->seg_tok_len[par]) {
           group_of[s] = g;
+          if (!is_cached(s)) add_live(g, p->groups[g].len, p->groups[g].len + t->seg_tok_len[s]);
           p->groups[g].len += t->seg_tok_len[s];
           group_last[g] = s;
           continue;
@@ -230,6 +239,8 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
       group_of[s] = static_cast<int32_t>(p->groups.size());
       group_last.push_back(s);
       p->groups.push_back(rg);
+      live_rows.emplace_back();
+      if (!is_cached(s)) add_live(group_of[s], 0, rg.len);
     }
   }
   p->tok_group.assign(t->n_tokens, -1);
@@ -238,8 +249,17 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
     const sp::RowGroup &rg = p->groups[g];
     std::fill(p->tok_group.begin() + rg.tok_start, p->tok_group.begin() + rg.tok_start + rg.len,
               static_cast<int32_t>(g));
-    p->visible_pairs += int64_t(rg.len) * rg.anc_keys + int64_t(rg.len) * (rg.len + 1) / 2;
+    for (auto &iv : live_rows[g]) {                       // pairs of the rows that are computed
+      const int64_t n = iv.second - iv.first;
+      p->visible_pairs += n * rg.anc_keys + (int64_t(iv.second) * (iv.second + 1) - int64_t(iv.first) * (iv.first + 1)) / 2;
+    }
   }
+  // device copy of the token -> group map: tokens of cached segments produce no rows
+  p->tok_group_dev = p->tok_group;
+  for (int32_t s = 0; s < S; ++s)
+    if (is_cached(s))
+      std::fill(p->tok_group_dev.begin() + t->seg_tok_start[s],
+                p->tok_group_dev.begin() + t->seg_tok_start[s] + t->seg_tok_len[s], -1);
 
   // --- prefill work list.  Query heads that share a KV head are stacked in one workgroup
   // (4 waves for 4 heads, else 2 waves), each wave owning 32 token rows of one head.
@@ -250,21 +270,24 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
   const int32_t n_hg = n_q_heads / p->heads_per_wg;
   {
     size_t g = 0;
-    std::vector<std::pair<int32_t, int32_t>> tiles;   // (group, row0) of the current prompt
+    struct Tile { int32_t group, row0, n_rows; };
+    std::vector<Tile> tiles;                          // tiles of the current prompt
     for (int32_t b = 0; b < B; ++b) {
       tiles.clear();
       for (; g < p->groups.size() && p->groups[g].prompt == b; ++g)
-        for (int32_t r = 0; r < p->groups[g].len; r += p->tile_rows) tiles.push_back({int32_t(g), r});
+        for (auto &iv : live_rows[g])
+          for (int32_t r = iv.first; r < iv.second; r += p->tile_rows)
+            tiles.push_back({int32_t(g), r, std::min(p->tile_rows, iv.second - r)});
       p->n_tiles += static_cast<int32_t>(tiles.size());
       // Order: all tiles of one (prompt, head group) are adjacent, so workgroups that read the
       // same K/V rows run close together in time and, after the XCD remap in the kernel, on
       // the same L2.
       for (int32_t hg = 0; hg < n_hg; ++hg)
         for (auto &tl : tiles) {
-          const sp::RowGroup &rg = p->groups[tl.first];
+          const sp::RowGroup &rg = p->groups[tl.group];
           sp::WorkItem w{};
-          w.tok_start = rg.tok_start; w.row0 = tl.second;
-          w.n_rows = std::min(p->tile_rows, rg.len - tl.second);
+          w.tok_start = rg.tok_start; w.row0 = tl.row0;
+          w.n_rows = tl.n_rows;
           w.anc_keys = rg.anc_keys; w.range_off = rg.range_off; w.n_ranges = rg.n_ranges;
           w.head0 = hg * p->heads_per_wg;
           w.r0_start = rg.n_ranges > 0 ? p->ranges[rg.range_off].tok_start : 0;
@@ -357,7 +380,7 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
     up(o_ranges, p->ranges.data(), p->ranges.size() * sizeof(sp::KeyRange));
     up(o_items, p->items.data(), p->items.size() * sizeof(sp::WorkItem));
     up(o_wgb, p->wg_begin.data(), p->wg_begin.size() * 4);
-    up(o_tokg, p->tok_group.data(), p->tok_group.size() * 4);
+    up(o_tokg, p->tok_group_dev.data(), p->tok_group_dev.size() * 4);
     up(o_pos, pos.data(), pos.size() * 4);
     up(o_slopes, slopes.data(), slopes.size() * 4);
     up(o_poff, p->path_off.data(), p->path_off.size() * 4);

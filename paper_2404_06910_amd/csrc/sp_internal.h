@@ -97,7 +97,8 @@ struct sp_plan {
   std::vector<sp::KeyRange> ranges;
   std::vector<sp::WorkItem> items;
   std::vector<int32_t> wg_begin;
-  std::vector<int32_t> tok_group;
+  std::vector<int32_t> tok_group;      // token -> row group (host inspection)
+  std::vector<int32_t> tok_group_dev;  // the same with tokens of cached segments set to -1
   std::vector<int32_t> path_off, shared_rng_beg, shared_rng_end, path_rng_beg, path_rng_end;
   std::vector<sp::KeyRange> dec_ranges;
   std::vector<int32_t> path_max_ranges;  // per prompt: max ranges of any single path

@@ -19,9 +19,9 @@ def dev(x, dtype="f32"):
     return t.cuda()
 
 
-def make_plan(ctx, st, Hq, Hkv, d, dtype, tok_pos=None, slopes=None):
+def make_plan(ctx, st, Hq, Hkv, d, dtype, tok_pos=None, slopes=None, seg_cached=None):
     return B.Plan(ctx, st.prompt_seg_off, st.seg_tok_start, st.seg_tok_len, st.seg_parent, st.seg_path, st.n_tokens,
-                  Hq, Hkv, d, SP_DT[dtype], tok_pos=tok_pos, alibi_slopes=slopes)
+                  Hq, Hkv, d, SP_DT[dtype], tok_pos=tok_pos, alibi_slopes=slopes, seg_cached=seg_cached)
 
 
 def run_prefill(ctx, st, q, k, v, dtype, scale=None, tok_pos=None, slopes=None, plan=None):

@@ -106,6 +106,67 @@ def test_general_tree_with_gaps_and_untouched_rows(ctx):
         assert np.all(got[np.isnan(ref)] == 7.0)            # uncovered tokens are left untouched
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_cached_segments_random_trees(ctx, dtype):
+    # Sec. 3.3.1 / Alg. 2: cached segments serve as keys; their output rows are not produced
+    from test_host_plan import _random_table
+    for seed in (21, 22, 23):
+        rng = np.random.default_rng(seed)
+        t = _random_table(rng, 3, scramble=seed != 22)
+        T = t["n_tokens"]; S = len(t["seg_parent"])
+        cached = (rng.random(S) < 0.5).astype(np.uint8)
+        q, k, v = _rand(rng, T, 4, 2, 64, dtype)
+        print("case: cached random tree seed", seed, dtype, "tokens", T, flush=True)
+        plan = B.Plan(ctx, t["prompt_seg_off"], t["seg_tok_start"], t["seg_tok_len"], t["seg_parent"], t["seg_path"], T,
+                      4, 2, 64, B.SP_BF16 if dtype == "bf16" else B.SP_F32, seg_cached=cached)
+        Q, K, V = dev(q, dtype), dev(k, dtype), dev(v, dtype)
+        O = torch.full_like(Q, 7.0)
+        ctx.sp_forkjoin_prefill(plan, Q, K, V, O, 0.125)
+        torch.cuda.synchronize()
+        got = O.float().cpu().numpy()
+        ref = orc.forkjoin_prefill(q, k, v, t["prompt_seg_off"], t["seg_tok_start"], t["seg_tok_len"], t["seg_parent"], 0.125)
+        for s in range(S):
+            if cached[s]:
+                ref[t["seg_tok_start"][s]:t["seg_tok_start"][s] + t["seg_tok_len"][s]] = np.nan
+        if not np.isnan(ref).all():
+            check_attn(got, ref, dtype, "cached tree %d" % seed)
+        assert np.all(got[np.isnan(ref)] == 7.0)            # cached and uncovered rows are left untouched
+
+
+@pytest.mark.parametrize("packing", ["interleaved", "grouped"])
+def test_split_phase_prefill_equals_one_pass(ctx, packing):
+    """Path caching (Sec. 3.3.1): preamble and documents are processed ahead of time, the query
+    copies online against the cached K/V. The online pass computes the query rows only and they
+    agree with the one-pass result (same oracle)."""
+    rng = np.random.default_rng(31)
+    lens = [[150, 64, 201], [97, 130]]
+    P, Lq, Hq, Hkv, d = 70, 19, 8, 2, 128
+    st = sp_synth.forkjoin_segtable(P, lens, Lq, packing)
+    q, k, v = _rand(rng, st.n_tokens, Hq, Hkv, d, "bf16")
+    print("case: split phase", packing, flush=True)
+    is_query = np.zeros(st.n_segments, bool); is_query[np.asarray(st.query_seg)] = True
+    ref = _oracle(st, q, k, v, 1 / math.sqrt(d))
+    one_pass, _ = run_prefill(ctx, st, q, k, v, "bf16")
+    offline = make_plan(ctx, st, Hq, Hkv, d, "bf16", seg_cached=is_query.astype(np.uint8))      # query rows skipped
+    online = make_plan(ctx, st, Hq, Hkv, d, "bf16", seg_cached=(~is_query).astype(np.uint8))    # query rows only
+    assert offline.visible_pairs() + online.visible_pairs() == make_plan(ctx, st, Hq, Hkv, d, "bf16").visible_pairs()
+    Q, K, V = dev(q, "bf16"), dev(k, "bf16"), dev(v, "bf16")
+    O = torch.full_like(Q, float("nan"))
+    ctx.sp_forkjoin_prefill(offline, Q, K, V, O, 1 / math.sqrt(d))
+    torch.cuda.synchronize()
+    qrow = np.zeros(st.n_tokens, bool)
+    for s in np.asarray(st.query_seg):
+        qrow[st.seg_tok_start[s]:st.seg_tok_start[s] + st.seg_tok_len[s]] = True
+    after_offline = O.float().cpu().numpy()
+    assert np.isnan(after_offline[qrow]).all() and not np.isnan(after_offline[~qrow]).any()
+    ctx.sp_forkjoin_prefill(online, Q, K, V, O, 1 / math.sqrt(d))
+    torch.cuda.synchronize()
+    got = O.float().cpu().numpy()
+    check_attn(got, ref, "bf16", "split phase")
+    assert np.array_equal(got[~qrow], after_offline[~qrow])             # the online pass writes query rows only
+    assert np.abs(got - one_pass).max() <= 2e-2
+
+
 def test_independence_of_paths_is_bitwise(ctx):
     rng = np.random.default_rng(5)
     st = sp_synth.forkjoin_segtable(64, [[128, 90, 128]], 24)

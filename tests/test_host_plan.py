@@ -93,6 +93,28 @@ def test_planner_key_lists_match_oracle_mask(seed):
         assert p.joined_keys(b, [-1] + kept).tolist() == want.tolist()      # negative entries are ignored
 
 
+@pytest.mark.parametrize("seed", range(4))
+def test_cached_segments_are_keys_only(seed):
+    # Sec. 3.3.1 / Alg. 2: segments whose K/V come from a path cache produce no query rows
+    rng = np.random.default_rng(100 + seed)
+    t = _random_table(rng, 3, scramble=seed % 2 == 0)
+    S = len(t["seg_parent"])
+    cached = (rng.random(S) < 0.5).astype(np.uint8)
+    p = _plan(t, seg_cached=cached)
+    pairs = 0
+    for b in range(3):
+        segs = list(range(t["prompt_seg_off"][b], t["prompt_seg_off"][b + 1]))
+        toks, M = orc.dag_mask(t["seg_tok_start"], t["seg_tok_len"], t["seg_parent"], segs)
+        live = np.concatenate([np.full(t["seg_tok_len"][s], not cached[s]) for s in segs]) if segs else np.zeros(0, bool)
+        pairs += int(M[live].sum())
+    assert p.visible_pairs() == pairs
+    full = _plan(t)
+    assert p.info()["n_row_groups"] == full.info()["n_row_groups"]      # key structure unchanged
+    assert p.info()["n_tiles"] <= full.info()["n_tiles"]
+    none = _plan(t, seg_cached=np.ones(S, np.uint8))
+    assert none.visible_pairs() == 0 and none.info()["n_tiles"] == 0
+
+
 def test_forkjoin_groups_tiles_and_pairs():
     wl = sp_synth.WORKLOADS["c2_mha7b_bf16"]
     st = sp_synth.forkjoin_segtable(wl.preamble_len, [[wl.doc_len] * wl.n_paths] * 2, wl.query_len)
