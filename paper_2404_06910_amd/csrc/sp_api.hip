@@ -7,6 +7,7 @@
 #include <cstring>
 #include <new>
 #include <numeric>
+#include <queue>
 
 #include "sp_internal.h"
 
@@ -275,9 +276,14 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
     for (int32_t b = 0; b < B; ++b) {
       tiles.clear();
       for (; g < p->groups.size() && p->groups[g].prompt == b; ++g)
-        for (auto &iv : live_rows[g])
-          for (int32_t r = iv.first; r < iv.second; r += p->tile_rows)
-            tiles.push_back({int32_t(g), r, std::min(p->tile_rows, iv.second - r)});
+        // A tile streams every key up to its last row, so the partial tile of an interval goes
+        // first, where that stream is shortest, and the full tiles end at the interval's end.
+        for (auto &iv : live_rows[g]) {
+          const int32_t rem = (iv.second - iv.first) % p->tile_rows;
+          if (rem) tiles.push_back({int32_t(g), iv.first, rem});
+          for (int32_t r = iv.first + rem; r < iv.second; r += p->tile_rows)
+            tiles.push_back({int32_t(g), r, p->tile_rows});
+        }
       p->n_tiles += static_cast<int32_t>(tiles.size());
       // Order: all tiles of one (prompt, head group) are adjacent, so workgroups that read the
       // same K/V rows run close together in time and, after the XCD remap in the kernel, on
@@ -289,18 +295,20 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
           w.tok_start = rg.tok_start; w.row0 = tl.row0;
           w.n_rows = tl.n_rows;
           w.anc_keys = rg.anc_keys; w.range_off = rg.range_off; w.n_ranges = rg.n_ranges;
-          w.head0 = hg * p->heads_per_wg;
+          w.head0 = (hg * p->heads_per_wg) | ((hg * p->heads_per_wg / G) << 16);
           w.r0_start = rg.n_ranges > 0 ? p->ranges[rg.range_off].tok_start : 0;
           p->items.push_back(w);
         }
     }
   }
-  // Persistent workgroups, 8 waves per compute unit.  The work list is cut into 8 contiguous,
-  // cost-balanced ranges, one per XCD (cost = LDS stages streamed: one for Q plus the K/V stages,
-  // plus the epilogue); inside a range the items are dealt round-robin to that XCD's workgroups.
-  // At any moment an XCD therefore works on a window of consecutive items -- all tiles of a path
-  // and the paths of one (prompt, KV head) -- so that every K/V row is fetched from HBM once and
-  // then found in that XCD's L2 by the other tiles that need it.
+  // Persistent workgroups, 8 waves per compute unit.  The work list (ordered prompt, head group,
+  // tile) is cut into 8 contiguous, cost-balanced ranges, one per XCD (cost = LDS stages streamed:
+  // one for Q plus the K/V stages, plus the epilogue).  Inside a range the items are handed out in
+  // order, each to the workgroup with the least work so far -- the schedule a shared queue would
+  // produce.  At any moment an XCD therefore works on a window of consecutive items (all tiles of a
+  // path, the paths of one (prompt, KV head)), so a K/V row fetched from HBM is found in that XCD's
+  // L2 by the other tiles that need it, and no workgroup ends much later than the others.
+  // The items are stored permuted so that every workgroup reads one contiguous slice.
   {
     int n_cu = 256;
     if (ctx) {
@@ -310,17 +318,43 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
     }
     const int32_t stage_keys = 16 * p->waves_per_wg;
     p->n_wg = (((8 / p->waves_per_wg) * n_cu + 7) / 8) * 8;
+    const int32_t xcd_wgs = p->n_wg / 8;
+    auto cost = [&](const sp::WorkItem &w) {
+      return int64_t(2 + (w.anc_keys + w.row0 + w.n_rows + stage_keys - 1) / stage_keys);
+    };
     int64_t total = 0;
-    auto stages = [&](const sp::WorkItem &w) { return (w.anc_keys + w.row0 + w.n_rows + stage_keys - 1) / stage_keys; };
-    for (auto &w : p->items) total += 2 + stages(w);
-    p->wg_begin.assign(9, static_cast<int32_t>(p->items.size()));
-    p->wg_begin[0] = 0;
-    int64_t acc = 0;
-    int32_t c = 1;
-    for (size_t i = 0; i < p->items.size() && c < 8; ++i) {
-      acc += 2 + stages(p->items[i]);
-      while (c < 8 && acc * 8 >= total * c) p->wg_begin[c++] = static_cast<int32_t>(i + 1);
+    for (auto &w : p->items) total += cost(w);
+    std::vector<size_t> xcd_begin(9, p->items.size());
+    xcd_begin[0] = 0;
+    {
+      int64_t acc = 0;
+      int32_t c = 1;
+      for (size_t i = 0; i < p->items.size() && c < 8; ++i) {
+        acc += cost(p->items[i]);
+        while (c < 8 && acc * 8 >= total * c) xcd_begin[c++] = i + 1;
+      }
     }
+    std::vector<std::vector<int32_t>> mine(p->n_wg);
+    for (int32_t x = 0; x < 8; ++x) {
+      // (work so far, workgroup) min-heap; ties go to the lower workgroup
+      std::priority_queue<std::pair<int64_t, int32_t>, std::vector<std::pair<int64_t, int32_t>>,
+                          std::greater<std::pair<int64_t, int32_t>>> heap;
+      for (int32_t w = 0; w < xcd_wgs; ++w) heap.push({0, w});
+      for (size_t i = xcd_begin[x]; i < xcd_begin[x + 1]; ++i) {
+        auto top = heap.top();
+        heap.pop();
+        mine[x * xcd_wgs + top.second].push_back(static_cast<int32_t>(i));
+        heap.push({top.first + cost(p->items[i]), top.second});
+      }
+    }
+    std::vector<sp::WorkItem> permuted;
+    permuted.reserve(p->items.size());
+    p->wg_begin.assign(p->n_wg + 1, 0);
+    for (int32_t g = 0; g < p->n_wg; ++g) {
+      for (int32_t i : mine[g]) permuted.push_back(p->items[i]);
+      p->wg_begin[g + 1] = static_cast<int32_t>(permuted.size());
+    }
+    p->items.swap(permuted);
   }
 
   // --- decode gather tables: shared ranges per prompt, ranges per path slot
@@ -495,8 +529,8 @@ extern "C" sp_status sp_forkjoin_prefill(sp_ctx *ctx, const sp_plan *plan, const
   if (q_head_stride < d || kv_head_stride < d || q_tok_stride < q_head_stride * 1 || kv_tok_stride < kv_head_stride * 1 ||
       q_tok_stride < d || kv_tok_stride < d)
     return fail(&ctx->err, SP_ERR_INVALID_ARG, "strides smaller than head_dim");
-  if (q_tok_stride >= (int64_t(1) << 31) || kv_tok_stride >= (int64_t(1) << 31))
-    return fail(&ctx->err, SP_ERR_UNSUPPORTED, "token strides must be below 2^31 elements");
+  if (q_tok_stride >= (int64_t(1) << 26) || kv_tok_stride >= (int64_t(1) << 26))
+    return fail(&ctx->err, SP_ERR_UNSUPPORTED, "token strides must be below 2^26 elements");
   const int64_t align = plan->dtype == SP_BF16 ? 8 : 4;   // 16-byte vector loads
   if (q_tok_stride % align || q_head_stride % align || kv_tok_stride % align || kv_head_stride % align)
     return fail(&ctx->err, SP_ERR_UNSUPPORTED, "strides must be multiples of %lld elements", (long long)align);

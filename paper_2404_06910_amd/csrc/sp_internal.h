@@ -40,7 +40,7 @@ struct WorkItem {
   int32_t anc_keys;    // keys in the ancestor ranges
   int32_t range_off;   // first ancestor range
   int32_t n_ranges;
-  int32_t head0;       // first query head handled by the workgroup
+  int32_t head0;       // first query head handled by the workgroup | its KV head << 16
   int32_t r0_start;    // first token of ancestor range 0 (the only one when n_ranges == 1)
 };
 
@@ -49,7 +49,7 @@ struct PlanDev {
   const RowGroup *groups;
   const KeyRange *ranges;
   const WorkItem *items;
-  const int32_t *wg_begin;       // [9] contiguous range of the work list per XCD
+  const int32_t *wg_begin;       // [n_wg + 1] slice of the (permuted) work list per workgroup slot
   const int32_t *tok_group;      // [n_tokens] row group of each token, -1 = uncovered
   const float *tok_pos;          // [n_tokens] or nullptr
   const float *slopes;           // [n_q_heads] or nullptr

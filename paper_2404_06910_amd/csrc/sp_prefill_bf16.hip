@@ -12,7 +12,7 @@
 // Workgroup = NW waves = NW blocks of 32 query rows: HPW query heads that share one KV head times
 // NW/HPW blocks of 32 tokens (4 waves when 4 heads share a KV head; else 2 waves, so that the
 // causal imbalance between early and late row blocks stays inside a pair).  Workgroups are
-// persistent: each owns a contiguous, cost-balanced slice of the work list (staged in LDS) and
+// persistent: each owns a cost-balanced slice of the (permuted) work list, staged in LDS, and
 // streams one unbroken sequence of LDS stages through a double buffer -- for every item first its
 // Q tile (32*NW rows = one stage), then its K/V tiles of 16*NW keys -- so the global loads of the
 // next stage (also across item boundaries) are in flight behind the current stage's math and no
@@ -78,16 +78,16 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
   __shared__ float Ps[2][BK];
   __shared__ __attribute__((aligned(16))) WorkItem s_items[kItemBatch];
 
-  // Workgroup ids are dealt round-robin over the 8 XCDs (id % 8).  Every XCD owns a contiguous range
-  // of the work list and deals its items round-robin to its workgroups, so the workgroups of an XCD
-  // work on a moving window of consecutive items and share their K/V rows through that XCD's L2.
-  const int xcd_wgs = pd.n_wg / 8, wg_in_xcd = blockIdx.x / 8;
-  const int x0 = pd.wg_begin[blockIdx.x % 8], x1 = pd.wg_begin[blockIdx.x % 8 + 1];
-  const int n_mine = (x1 - x0 - wg_in_xcd + xcd_wgs - 1) / xcd_wgs;   // items x0 + wg_in_xcd + k * xcd_wgs
-  if (x1 - x0 - wg_in_xcd <= 0) return;
+  // Workgroup ids are dealt round-robin over the 8 XCDs (id % 8).  The host has given every XCD a
+  // contiguous range of the work list and handed its items out in order to that XCD's workgroup
+  // slots, so the workgroups of an XCD work on a moving window of consecutive items and share
+  // their K/V rows through that XCD's L2.  Slot s = xcd * (n_wg / 8) + id / 8 owns items [x0, x1).
+  const int wg_slot = (blockIdx.x % 8) * (pd.n_wg / 8) + blockIdx.x / 8;
+  const int x0 = pd.wg_begin[wg_slot], x1 = pd.wg_begin[wg_slot + 1];
+  const int n_mine = x1 - x0;
+  if (n_mine <= 0) return;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
-  const int G = pd.n_q_heads / pd.n_kv_heads;
   const int tr_row = (lane & 15) >> 2;                          // transpose-read source: key row within 4
   const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);   // and first of 4 dims within 32
   const float scale2 = scale * kLog2e;
@@ -96,8 +96,19 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
   u32x4 areg[LOADS], breg[LOADS];
   float preg = 0.f;
 
+  // a work item as the loop keeps it (all fields wave-uniform)
+  struct Item {
+    int tok_start, row0, n_rows, anc_keys, range_off, n_ranges, head0, kv_head, r0_start;
+  };
+  // Byte offsets of this thread inside a load pass; a pass covers RPP consecutive rows, so for runs
+  // of consecutive tokens everything else about an address is wave-uniform (scalar base + this).
+  const uint32_t kv_lane_off = ((uint32_t)lrow * kv_ts + lcol) * 2;
+  const uint32_t q_lane_off = ((uint32_t)lrow * q_ts + lcol) * 2;
+  const char *Qb = reinterpret_cast<const char *>(Q), *Kb = reinterpret_cast<const char *>(K),
+             *Vb = reinterpret_cast<const char *>(V);
+
   // virtual key -> packed token for item w
-  auto map_tok = [&](const WorkItem &w, int vk) -> int {
+  auto map_tok = [&](const Item &w, int vk) -> int {
     vk = min(vk, w.anc_keys + w.row0 + w.n_rows - 1);           // past the end: re-read the last key (masked)
     if (vk >= w.anc_keys) return w.tok_start + (vk - w.anc_keys);
     if (w.n_ranges == 1) return w.r0_start + vk;
@@ -110,8 +121,22 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
     return tok;
   };
   // issue the global loads of stage st of item w (st = -1: the Q tile)
-  auto gload = [&](const WorkItem &w, int st) {
+  auto gload = [&](const Item &w, int st) {
     if (st < 0) {
+      if (w.n_rows == 32 * NW / HPW) {
+        // full tile: row r = lrow + m*RPP sits in 32-row slot (m*RPP)/32 at (m*RPP)%32 + lrow
+        const uint64_t t0 = (uint32_t)(w.tok_start + w.row0);
+#pragma unroll
+        for (int m = 0; m < LOADS; ++m) {
+          const int ra = m * RPP, rb = BK + m * RPP;              // compile-time row bases of the two halves
+          const int sa = ra >> 5, sb = rb >> 5;
+          const uint64_t oa = ((t0 + 32 * (sa / HPW) + (ra & 31)) * q_ts + (uint64_t)(uint32_t)(w.head0 + sa % HPW) * q_hs) * 2;
+          const uint64_t ob = ((t0 + 32 * (sb / HPW) + (rb & 31)) * q_ts + (uint64_t)(uint32_t)(w.head0 + sb % HPW) * q_hs) * 2;
+          areg[m] = ld16(Qb + oa + q_lane_off);
+          breg[m] = ld16(Qb + ob + q_lane_off);
+        }
+        return;
+      }
 #pragma unroll
       for (int m = 0; m < LOADS; ++m) {
         const int r = lrow + m * RPP;                           // Q-tile rows r and BK + r
@@ -122,7 +147,27 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
         breg[m] = ld16(Q + ((uint64_t)(uint32_t)t1 * q_ts + (uint32_t)(w.head0 + s1 % HPW) * q_hs + lcol));
       }
     } else {
-      const uint32_t hoff = (uint32_t)(w.head0 / G) * kv_hs + lcol;
+      // A stage whose BK keys are consecutive tokens (inside the own run and not past its end, or
+      // inside a single ancestor range) needs no per-lane address arithmetic.
+      const int vk0 = st * BK;
+      int tok0 = -1;
+      if (vk0 >= w.anc_keys) {
+        if (vk0 + BK <= w.anc_keys + w.row0 + w.n_rows) tok0 = w.tok_start + (vk0 - w.anc_keys);
+      } else if (w.n_ranges == 1 && vk0 + BK <= w.anc_keys) {
+        tok0 = w.r0_start + vk0;
+      }
+      if (tok0 >= 0) {
+        const uint64_t o0 = ((uint64_t)(uint32_t)tok0 * kv_ts + (uint64_t)(uint32_t)w.kv_head * kv_hs) * 2;
+#pragma unroll
+        for (int m = 0; m < LOADS; ++m) {
+          const uint64_t o = o0 + (uint64_t)(m * RPP) * kv_ts * 2;
+          areg[m] = ld16(Kb + o + kv_lane_off);
+          breg[m] = ld16(Vb + o + kv_lane_off);
+        }
+        if (BIAS && tid < BK) preg = pd.tok_pos[tok0 + tid];
+        return;
+      }
+      const uint32_t hoff = (uint32_t)w.kv_head * kv_hs + lcol;
 #pragma unroll
       for (int m = 0; m < LOADS; ++m) {
         const uint64_t off = (uint64_t)(uint32_t)map_tok(w, st * BK + lrow + m * RPP) * kv_ts + hoff;
@@ -142,17 +187,19 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
   };
 
   // Work items are read from an LDS copy of the slice (no pointer chasing in the stream loop).
-  auto fetch_item = [&](int local) -> WorkItem {          // local index inside the staged batch
+  auto fetch_item = [&](int local) -> Item {              // local index inside the staged batch
     const int4 a = *reinterpret_cast<const int4 *>(&s_items[local]);
     const int4 b = *(reinterpret_cast<const int4 *>(&s_items[local]) + 1);
-    WorkItem w;
+    Item w;
     w.tok_start = __builtin_amdgcn_readfirstlane(a.x); w.row0 = __builtin_amdgcn_readfirstlane(a.y);
     w.n_rows = __builtin_amdgcn_readfirstlane(a.z); w.anc_keys = __builtin_amdgcn_readfirstlane(a.w);
     w.range_off = __builtin_amdgcn_readfirstlane(b.x); w.n_ranges = __builtin_amdgcn_readfirstlane(b.y);
-    w.head0 = __builtin_amdgcn_readfirstlane(b.z); w.r0_start = __builtin_amdgcn_readfirstlane(b.w);
+    const int heads = __builtin_amdgcn_readfirstlane(b.z);    // query head | KV head << 16
+    w.head0 = heads & 0xffff; w.kv_head = heads >> 16;
+    w.r0_start = __builtin_amdgcn_readfirstlane(b.w);
     return w;
   };
-  auto n_stages = [](const WorkItem &w) { return (w.anc_keys + w.row0 + w.n_rows + BK - 1) / BK; };
+  auto n_stages = [](const Item &w) { return (w.anc_keys + w.row0 + w.n_rows + BK - 1) / BK; };
 
   bf16x8 qf[NJ];
   f32x16 o[NC];
@@ -164,10 +211,10 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
     __syncthreads();                                     // previous batch fully consumed
     for (int i = tid; i < (it_end - it) * 2; i += T)
       reinterpret_cast<int4 *>(s_items)[i] =
-          reinterpret_cast<const int4 *>(pd.items + (x0 + wg_in_xcd + (int64_t)(it + (i >> 1)) * xcd_wgs))[i & 1];
+          reinterpret_cast<const int4 *>(pd.items + (x0 + it + (i >> 1)))[i & 1];
     __syncthreads();
-    WorkItem cur = fetch_item(0);
-    WorkItem nxt = cur;
+    Item cur = fetch_item(0);
+    Item nxt = cur;
     if (it + 1 < it_end) nxt = fetch_item(1);
     int st = -1;                       // current stage of the current item
     int buf = 0;
