@@ -40,6 +40,7 @@ constexpr int kItemBatch = 32;     // work items staged in LDS at a time
 #define SP_PADV 8
 #endif
 typedef bf16x4 __attribute__((address_space(3))) lds_bf16x4;
+typedef unsigned char __attribute__((address_space(3))) lds_byte;
 
 // max / sum partner exchange between lane L and lane L^32 (v_permlane32_swap)
 __device__ __forceinline__ float xhalf_max(float x) {
@@ -51,6 +52,13 @@ __device__ __forceinline__ float xhalf_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// LDS-DMA: every lane moves 16 bytes from its global address straight into LDS byte
+// (lds_base + 16 * lane); no staging registers.  The compiler does not track these loads:
+// completion is awaited with an explicit s_waitcnt vmcnt(0) before the stage barrier.
+__device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory", "m0");
+}
+
 template <int D, int HPW, int NW, bool BIAS>
 __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, const __bf16 *__restrict__ Q,
                                                                   const __bf16 *__restrict__ K,
@@ -60,23 +68,27 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
                                                                   float scale) {
   constexpr int T = 64 * NW;               // threads
   constexpr int BK = 16 * NW;              // keys per K/V stage; a stage holds 2*BK = 32*NW rows
-  constexpr int LDK = D + SP_PADK;         // padded LDS rows of the K half (16-byte row reads)
-  constexpr int LDV = D + SP_PADV;         // and of the V half (transpose reads of 4 keys x 16 dims)
+  constexpr int ROWB = D * 2;              // bytes per LDS row (unpadded)
   constexpr int CPR = D / 8;               // 16-byte chunks per row
-  constexpr int RPP = T / CPR;             // rows covered by one pass of all threads
-  constexpr int LOADS = BK / RPP;          // passes per half stage
+  constexpr int RPC = 256 / ROWB;          // rows per 256 bytes (1 or 2)
+  constexpr int RG = 64 / CPR;             // rows moved by one wave-wide DMA instruction (4 or 8)
+  constexpr int NDMA = 32 / RG;            // DMA instructions per wave and stage: a wave fills 32 rows
+  constexpr int HALFB = BK * ROWB;         // bytes of the K half (= of the V half) of a stage
+  constexpr int STAGEB = 2 * HALFB;
   constexpr int NJ = D / 16;               // MFMAs along head_dim for S
   constexpr int NC = D / 32;               // 32-wide output blocks of O^T
-  static_assert(NW % HPW == 0 && BK % 32 == 0 || BK == 32, "tile shape");
+  static_assert(NW % HPW == 0 && NW % 2 == 0, "tile shape");
+  static_assert(2 * STAGEB <= 65536, "DMA destinations are kept below 64 KB");
 
-  // A stage is BK K rows + BK V rows; a Q tile (2*BK rows) uses the K half for rows 0..BK and the
-  // V half for rows BK..2BK.
-  __shared__ __attribute__((aligned(16))) __bf16 stK[2][BK][LDK];
-  __shared__ __attribute__((aligned(16))) __bf16 stV[2][BK][LDV];
-  // row r of the 2*BK-row view of a stage
-  auto srow = [&](int buf, int r) -> __bf16 * { return r < BK ? &stK[buf][r][0] : &stV[buf][r - BK][0]; };
+  // Two stage slots.  A slot is 2*BK rows: K rows then V rows (a Q tile uses all 2*BK rows).  Rows
+  // are unpadded (the DMA writes 1 KB runs); instead the 16-byte chunks of a row are XOR-swizzled
+  // on the global-address side, so that the row reads of K and Q (ds_read_b128, 16 consecutive rows,
+  // same chunk) and the transpose reads of V (4 rows x 32 bytes per 16 lanes) spread over the banks.
+  __shared__ __attribute__((aligned(1024))) unsigned char ring[2 * STAGEB];
   __shared__ float Ps[2][BK];
   __shared__ __attribute__((aligned(16))) WorkItem s_items[kItemBatch];
+  auto fK = [](int row) { return (row / RPC) % CPR; };
+  auto fV = [](int row) { return 4 * ((row / RPC) % (CPR / 4)); };
 
   // Workgroup ids are dealt round-robin over the 8 XCDs (id % 8).  The host has given every XCD a
   // contiguous range of the work list and handed its items out in order to that XCD's workgroup
@@ -87,26 +99,43 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
   const int n_mine = x1 - x0;
   if (n_mine <= 0) return;
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
-  const int tr_row = (lane & 15) >> 2;                          // transpose-read source: key row within 4
-  const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);   // and first of 4 dims within 32
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31,
+            half = lane >> 5;
   const float scale2 = scale * kLog2e;
-  const int lrow = tid / CPR, lcol = (tid % CPR) * 8;           // this thread's row / column in a load pass
+  const uint32_t ring_base = (uint32_t)(size_t)(lds_byte *)ring;
+  unsigned char *const ringp = ring;
 
-  u32x4 areg[LOADS], breg[LOADS];
+  // ---- DMA geometry.  Wave w fills stage rows [32w, 32w + 32): the K half belongs to the first
+  // NW/2 waves, the V half to the others; a Q tile's 32-row slot w is filled by wave w.  One
+  // instruction moves RG rows; this lane writes chunk position (lane % CPR) of row (lane / CPR)
+  // of the group and therefore fetches the chunk that the swizzle maps there.
+  const int drow = lane / CPR, dslot = lane % CPR;
+  const bool dma_is_v = wave >= NW / 2;
+  const int rbase = 32 * (wave % (NW / 2));                   // first row of this wave inside its half
+  uint32_t xkv[NDMA];                                         // swizzled chunk byte offsets per instruction
+#pragma unroll
+  for (int m = 0; m < NDMA; ++m)
+    xkv[m] = (uint32_t)(dslot ^ (dma_is_v ? fV(rbase + RG * m + drow) : fK(rbase + RG * m + drow))) * 16;
+  auto xq = [&](int m) { return (uint32_t)(dslot ^ fK(RG * m + drow)) * 16; };   // Q tile: fK on every row
+  const uint32_t kv_row_off = (uint32_t)drow * kv_ts * 2, q_row_off = (uint32_t)drow * q_ts * 2;
+  const char *Qb = reinterpret_cast<const char *>(Q);
+  const char *KVb = reinterpret_cast<const char *>(dma_is_v ? V : K);
+
+  // ---- fragment-read geometry
+  // K / Q rows: row l32 (+ multiples of 32), chunk 2j + half  ->  ((2j) ^ (f & ~1)) | ((half ^ f) & 1)
+  const int kf_f = fK(l32), kf_lo = (half ^ kf_f) & 1, kf_fh = kf_f & ~1;
+  // V transpose read: source lane s of a 16-lane group hands in key row s/4, dims 4*(s%4)..+3 of a
+  // 16-dim block, and lane i receives dim i of the 4 keys.
+  const int tr_row = (lane & 15) >> 2;
+  const int tr_chlo = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1), tr_sub8 = (lane & 1) * 8;
+  const int tr_f = fV(4 * half + tr_row);                     // the other rows differ by multiples of 8
+
   float preg = 0.f;
 
   // a work item as the loop keeps it (all fields wave-uniform)
   struct Item {
     int tok_start, row0, n_rows, anc_keys, range_off, n_ranges, head0, kv_head, r0_start;
   };
-  // Byte offsets of this thread inside a load pass; a pass covers RPP consecutive rows, so for runs
-  // of consecutive tokens everything else about an address is wave-uniform (scalar base + this).
-  const uint32_t kv_lane_off = ((uint32_t)lrow * kv_ts + lcol) * 2;
-  const uint32_t q_lane_off = ((uint32_t)lrow * q_ts + lcol) * 2;
-  const char *Qb = reinterpret_cast<const char *>(Q), *Kb = reinterpret_cast<const char *>(K),
-             *Vb = reinterpret_cast<const char *>(V);
-
   // virtual key -> packed token for item w
   auto map_tok = [&](const Item &w, int vk) -> int {
     vk = min(vk, w.anc_keys + w.row0 + w.n_rows - 1);           // past the end: re-read the last key (masked)
@@ -120,35 +149,29 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
     }
     return tok;
   };
-  // issue the global loads of stage st of item w (st = -1: the Q tile)
-  auto gload = [&](const Item &w, int st) {
+  // issue this wave's DMA loads of stage st of item w (st = -1: the Q tile) into slot `slot`
+  auto issue = [&](const Item &w, int st, int slot) {
+    const uint32_t lds = ring_base + slot * STAGEB + wave * (32 * ROWB);
     if (st < 0) {
+      const int tb = 32 * (wave / HPW);                       // first tile row of this wave's Q rows
+      const uint64_t hoff = (uint64_t)(uint32_t)(w.head0 + wave % HPW) * q_hs * 2;
       if (w.n_rows == 32 * NW / HPW) {
-        // full tile: row r = lrow + m*RPP sits in 32-row slot (m*RPP)/32 at (m*RPP)%32 + lrow
-        const uint64_t t0 = (uint32_t)(w.tok_start + w.row0);
+        // full tile: consecutive tokens, everything but the lane's own offset is wave-uniform
+        const uint64_t o0 = (uint64_t)(uint32_t)(w.tok_start + w.row0 + tb) * q_ts * 2 + hoff;
 #pragma unroll
-        for (int m = 0; m < LOADS; ++m) {
-          const int ra = m * RPP, rb = BK + m * RPP;              // compile-time row bases of the two halves
-          const int sa = ra >> 5, sb = rb >> 5;
-          const uint64_t oa = ((t0 + 32 * (sa / HPW) + (ra & 31)) * q_ts + (uint64_t)(uint32_t)(w.head0 + sa % HPW) * q_hs) * 2;
-          const uint64_t ob = ((t0 + 32 * (sb / HPW) + (rb & 31)) * q_ts + (uint64_t)(uint32_t)(w.head0 + sb % HPW) * q_hs) * 2;
-          areg[m] = ld16(Qb + oa + q_lane_off);
-          breg[m] = ld16(Qb + ob + q_lane_off);
+        for (int m = 0; m < NDMA; ++m)
+          dma16(Qb + (o0 + (uint64_t)(RG * m) * q_ts * 2) + (q_row_off + xq(m)), lds + m * (RG * ROWB));
+      } else {
+#pragma unroll
+        for (int m = 0; m < NDMA; ++m) {
+          const int row = min(tb + RG * m + drow, w.n_rows - 1);   // rows past the tile repeat its last row
+          dma16(Qb + ((uint64_t)(uint32_t)(w.tok_start + w.row0 + row) * q_ts * 2 + hoff + xq(m)),
+                lds + m * (RG * ROWB));
         }
-        return;
-      }
-#pragma unroll
-      for (int m = 0; m < LOADS; ++m) {
-        const int r = lrow + m * RPP;                           // Q-tile rows r and BK + r
-        const int s0 = r >> 5, s1 = (BK + r) >> 5;              // their 32-row slots
-        const int t0 = w.tok_start + w.row0 + min(32 * (s0 / HPW) + (r & 31), w.n_rows - 1);
-        const int t1 = w.tok_start + w.row0 + min(32 * (s1 / HPW) + ((BK + r) & 31), w.n_rows - 1);
-        areg[m] = ld16(Q + ((uint64_t)(uint32_t)t0 * q_ts + (uint32_t)(w.head0 + s0 % HPW) * q_hs + lcol));
-        breg[m] = ld16(Q + ((uint64_t)(uint32_t)t1 * q_ts + (uint32_t)(w.head0 + s1 % HPW) * q_hs + lcol));
       }
     } else {
       // A stage whose BK keys are consecutive tokens (inside the own run and not past its end, or
-      // inside a single ancestor range) needs no per-lane address arithmetic.
+      // inside a single ancestor range) needs no per-lane token lookup.
       const int vk0 = st * BK;
       int tok0 = -1;
       if (vk0 >= w.anc_keys) {
@@ -156,34 +179,28 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
       } else if (w.n_ranges == 1 && vk0 + BK <= w.anc_keys) {
         tok0 = w.r0_start + vk0;
       }
+      const uint64_t hoff = (uint64_t)(uint32_t)w.kv_head * kv_hs * 2;
       if (tok0 >= 0) {
-        const uint64_t o0 = ((uint64_t)(uint32_t)tok0 * kv_ts + (uint64_t)(uint32_t)w.kv_head * kv_hs) * 2;
+        const uint64_t o0 = (uint64_t)(uint32_t)(tok0 + rbase) * kv_ts * 2 + hoff;
 #pragma unroll
-        for (int m = 0; m < LOADS; ++m) {
-          const uint64_t o = o0 + (uint64_t)(m * RPP) * kv_ts * 2;
-          areg[m] = ld16(Kb + o + kv_lane_off);
-          breg[m] = ld16(Vb + o + kv_lane_off);
-        }
+        for (int m = 0; m < NDMA; ++m)
+          dma16(KVb + (o0 + (uint64_t)(RG * m) * kv_ts * 2) + (kv_row_off + xkv[m]), lds + m * (RG * ROWB));
         if (BIAS && tid < BK) preg = pd.tok_pos[tok0 + tid];
-        return;
-      }
-      const uint32_t hoff = (uint32_t)w.kv_head * kv_hs + lcol;
+      } else {
 #pragma unroll
-      for (int m = 0; m < LOADS; ++m) {
-        const uint64_t off = (uint64_t)(uint32_t)map_tok(w, st * BK + lrow + m * RPP) * kv_ts + hoff;
-        areg[m] = ld16(K + off);
-        breg[m] = ld16(V + off);
+        for (int m = 0; m < NDMA; ++m) {
+          const int tok = map_tok(w, vk0 + rbase + RG * m + drow);
+          dma16(KVb + ((uint64_t)(uint32_t)tok * kv_ts * 2 + hoff + xkv[m]), lds + m * (RG * ROWB));
+        }
+        if (BIAS && tid < BK) preg = pd.tok_pos[map_tok(w, vk0 + tid)];
       }
-      if (BIAS && tid < BK) preg = pd.tok_pos[map_tok(w, st * BK + tid)];
     }
   };
-  auto sstore = [&](int buf) {
-#pragma unroll
-    for (int m = 0; m < LOADS; ++m) {
-      st16(&stK[buf][lrow + m * RPP][lcol], areg[m]);
-      st16(&stV[buf][lrow + m * RPP][lcol], breg[m]);
-    }
-    if (BIAS && tid < BK) Ps[buf][tid] = preg;
+  // all loads of this wave have landed; then meet the other waves
+  auto land_and_sync = [&](int slot) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (BIAS && tid < BK) Ps[slot][tid] = preg;
+    __syncthreads();
   };
 
   // Work items are read from an LDS copy of the slice (no pointer chasing in the stream loop).
@@ -219,18 +236,19 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
     int st = -1;                       // current stage of the current item
     int buf = 0;
 
-    gload(cur, -1);
-    sstore(0);
-    __syncthreads();
+    issue(cur, -1, 0);
+    land_and_sync(0);
 
     while (true) {
-      // which stage follows?  (K/V stage of this item, or the Q tile of the next item)
+      // which stage follows?  (K/V stage of this item, or the Q tile of the next item)  Its slot
+      // was last read before the barrier that ended the previous stage.
       const bool last_stage = st + 1 >= n_stages(cur);
       const bool have_next = !last_stage || it + 1 < it_end;
       if (have_next) {
-        if (!last_stage) gload(cur, st + 1);
-        else gload(nxt, -1);
+        if (!last_stage) issue(cur, st + 1, buf ^ 1);
+        else issue(nxt, -1, buf ^ 1);
       }
+      const unsigned char *sl = ringp + buf * STAGEB;
 
       // The 32-row block owned by this wave rotates with the item index so that the long
       // (late-row) blocks of the resident workgroups do not pile up on one SIMD.
@@ -246,9 +264,10 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
 
       if (st < 0) {
         // Q stage: pull this wave's Q fragment (B operand; k-slot block j covers dims [16j + 8*half, +8))
+        const unsigned char *qrow = sl + (32 * slot + l32) * ROWB;
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
-          qf[j] = *reinterpret_cast<const bf16x8 *>(srow(buf, 32 * slot + l32) + 16 * j + 8 * half);
+          qf[j] = *reinterpret_cast<const bf16x8 *>(qrow + ((((2 * j) ^ kf_fh) | kf_lo) * 16));
 #pragma unroll
         for (int c = 0; c < NC; ++c)
 #pragma unroll
@@ -268,9 +287,10 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
           f32x16 s;
 #pragma unroll
           for (int i = 0; i < 16; ++i) s[i] = 0.f;
+          const unsigned char *krow = sl + (32 * sub + l32) * ROWB;
 #pragma unroll
           for (int j = 0; j < NJ; ++j) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&stK[buf][32 * sub + l32][16 * j + 8 * half]);
+            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(krow + ((((2 * j) ^ kf_fh) | kf_lo) * 16));
             s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[j], s, 0, 0, 0);
           }
 
@@ -311,15 +331,16 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
             pb[i / 8][i % 8] = static_cast<__bf16>(p);
           }
           l_run += ls;
+          // V^T fragments through the LDS transpose read (4 keys x 16 dims per 16-lane group)
+          const unsigned char *vrow = sl + HALFB + (32 * sub + 4 * half + tr_row) * ROWB + tr_sub8;
 #pragma unroll
           for (int c = 0; c < NC; ++c) {
+            const int choff = (((4 * c) ^ tr_f) + tr_chlo) * 16;
 #pragma unroll
             for (int mm = 0; mm < 2; ++mm) {
-              // V^T fragment through the LDS transpose read: a 16-lane group hands in a 4-key x 16-dim
-              // block (lane s: key s/4, dims 4*(s%4)..+3) and lane i receives dim i of the 4 keys.
-              const __bf16 *vp = &stV[buf][32 * sub + 16 * mm + 4 * half + tr_row][32 * c + tr_col];
+              const unsigned char *vp = vrow + 16 * mm * ROWB + choff;
               const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)vp);
-              const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(vp + 8 * LDV));
+              const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(vp + 8 * ROWB));
               const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
               o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[mm], o[c], 0, 0, 0);
             }
@@ -333,7 +354,7 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
           __syncthreads();                                   // every wave is done reading this stage
           if (active) {
             const float inv = 1.f / xhalf_sum(l_run);
-            __bf16 *orow = srow(buf, 32 * wave + l32) + 4 * half;
+            unsigned char *orow = ringp + buf * STAGEB + (32 * wave + l32) * ROWB + 8 * half;
 #pragma unroll
             for (int c = 0; c < NC; ++c)
 #pragma unroll
@@ -341,7 +362,7 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
                 bf16x4 w4;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) w4[e] = static_cast<__bf16>(o[c][4 * q4 + e] * inv);
-                *reinterpret_cast<bf16x4 *>(orow + 32 * c + 8 * q4) = w4;
+                *reinterpret_cast<bf16x4 *>(orow + (((4 * c + q4) ^ kf_f) * 16)) = w4;
               }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -353,15 +374,15 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
               const int id = lane + 64 * i, row = id / CPR, ch = id % CPR;
               if (row < rows_here)
                 st16(ob + ((uint64_t)(uint32_t)row * q_ts + ch * 8),
-                     *reinterpret_cast<const u32x4 *>(srow(buf, 32 * wave + row) + ch * 8));
+                     *reinterpret_cast<const u32x4 *>(ringp + buf * STAGEB + (32 * wave + row) * ROWB +
+                                                      ((ch ^ fK(row)) * 16)));
             }
           }
         }
       }
 
       if (!have_next) break;
-      sstore(buf ^ 1);
-      __syncthreads();
+      land_and_sync(buf ^ 1);
       buf ^= 1;
       if (!last_stage) {
         ++st;
