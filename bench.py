@@ -138,6 +138,9 @@ def main():
     ap.add_argument("--workload", default="c2_mha7b_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode-c5", action="store_true")
+    ap.add_argument("--no-online-prefill", action="store_true",
+                    help="skip the path-cached (query rows only) prefill leg, e.g. so that a kernel trace of this "
+                         "run holds full prefill launches only")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="short run for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE: a plain elementwise kernel of known "
                          "traffic (calibration), then a few steps; prints no benchmark line")
@@ -255,7 +258,8 @@ def main():
         except Exception:
             pass
 
-    out["prefill_online_cached"] = _bench_online_prefill(ctx, torch, B, wl, sets, scale)
+    if not args.no_online_prefill:
+        out["prefill_online_cached"] = _bench_online_prefill(ctx, torch, B, wl, sets, scale)
     if not args.no_decode_c5:
         out["decode_c5"] = _bench_decode_c5(ctx, torch, B)
     if not args.no_cpu_baseline:

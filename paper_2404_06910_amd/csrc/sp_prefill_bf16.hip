@@ -13,10 +13,11 @@
 // NW/HPW blocks of 32 tokens (4 waves when 4 heads share a KV head; else 2 waves, so that the
 // causal imbalance between early and late row blocks stays inside a pair).  Workgroups are
 // persistent: each owns a cost-balanced slice of the (permuted) work list, staged in LDS, and
-// streams one unbroken sequence of LDS stages through a double buffer -- for every item first its
-// Q tile (32*NW rows = one stage), then its K/V tiles of 16*NW keys -- so the global loads of the
-// next stage (also across item boundaries) are in flight behind the current stage's math and no
-// item pays a cold start.  O^T tiles leave through LDS as whole 16-byte chunks of contiguous rows.
+// streams one unbroken sequence of stages through two LDS slots -- for every item first its Q tile
+// (32*NW rows = one stage), then its K/V tiles of 16*NW keys.  A stage is moved by LDS-DMA (global
+// memory straight into LDS, no staging registers) while the waves work on the other slot, also
+// across item boundaries, so no item pays a cold start; one barrier per stage.  O^T tiles leave
+// through LDS as whole 16-byte chunks of contiguous rows.
 //
 // Per wave and 32-key block, with the v_mfma_f32_32x32x16_bf16 tile shape:
 //   S^T[key, row]  = K[key, :] . Q[row, :]      A = K fragment (LDS), B = Q fragment (registers)
