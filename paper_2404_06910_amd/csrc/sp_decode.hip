@@ -45,29 +45,77 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(PlanDev pd, DecodeD
   const int tid = threadIdx.x, kg = tid / LPK, sub = tid % LPK;
   const bool bias = pd.slopes != nullptr;
 
-  __shared__ int32_t r_start[kDecMaxRanges], r_cum[kDecMaxRanges + 1];
+  __shared__ int32_t r_start[kDecMaxRanges], r_cum[kDecMaxRanges + 1], r_len[kDecMaxRanges];
+  __shared__ int32_t s_cnt[kDecMaxRanges], s_keys[kDecMaxRanges];
   __shared__ int32_t s_nr;
   __shared__ float s_m[KPW][GC], s_l[KPW][GC];
   __shared__ float s_acc[KPW][GC][D];
 
-  if (tid == 0) {
-    int n = 0, cum = 0;
-    auto add = [&](int beg, int end) {
-      for (int r = beg; r < end && n < kDecMaxRanges; ++r) {
-        r_start[n] = pd.dec_ranges[r].tok_start;
-        r_cum[n] = cum;
-        cum += pd.dec_ranges[r].len;
-        ++n;
+  // query chunk of this lane for each head, pre-scaled so that scores are in log2 units (requested
+  // first: these loads run under the table walk below)
+  float qf[GC][EV];
+  float slope2[GC];
+  const float pos_q = (bias && a.new_pos) ? a.new_pos[b] : 0.f;
+#pragma unroll
+  for (int c = 0; c < GC; ++c) {
+    const T *qp = static_cast<const T *>(a.q_new) + ((int64_t)b * Hq + head0 + c) * D + sub * EV;
+    Elem<T>::unpack(ld16(qp), qf[c]);
+#pragma unroll
+    for (int e = 0; e < EV; ++e) qf[c][e] *= a.scale * kLog2e;
+    slope2[c] = bias ? pd.slopes[head0 + c] * kLog2e : 0.f;
+  }
+
+  // The joined cache [shared ; kept path 0 ; ... ; kept path k-1] as a list of token ranges with
+  // running key counts.  Source 0 is the shared part, source j >= 1 the (j-1)-th kept path; one
+  // thread per source follows the tables (kept -> path slot -> ranges), so the dependent loads of
+  // all sources run side by side; two small prefix sums through LDS put the ranges in order.
+  {
+    const int n_src = min(a.k + 1, kDecMaxRanges);
+    int beg = 0, end = 0;
+    if (tid == 0) {
+      beg = pd.shared_rng_beg[b];
+      end = pd.shared_rng_end[b];
+    } else if (tid < n_src) {
+      const int p0 = pd.path_off[b], np = pd.path_off[b + 1] - p0;
+      const int kp = a.kept[(int64_t)b * a.k + (tid - 1)];
+      if (kp >= 0 && kp < np) {
+        beg = pd.path_rng_beg[p0 + kp];
+        end = pd.path_rng_end[p0 + kp];
       }
-    };
-    add(pd.shared_rng_beg[b], pd.shared_rng_end[b]);
-    const int np = pd.path_off[b + 1] - pd.path_off[b];
-    for (int j = 0; j < a.k; ++j) {
-      const int kp = a.kept[(int64_t)b * a.k + j];
-      if (kp >= 0 && kp < np) add(pd.path_rng_beg[pd.path_off[b] + kp], pd.path_rng_end[pd.path_off[b] + kp]);
     }
-    r_cum[n] = cum;
-    s_nr = n;
+    if (tid < n_src) s_cnt[tid] = end - beg;
+    __syncthreads();
+    int off = 0, keys = 0;
+    if (tid < n_src) {
+      for (int i = 0; i < tid; ++i) off += s_cnt[i];
+      for (int r = beg; r < end; ++r) {
+        const int at = off + (r - beg);
+        if (at < kDecMaxRanges) {
+          const KeyRange kr = pd.dec_ranges[r];
+          r_start[at] = kr.tok_start;
+          r_len[at] = kr.len;
+          keys += kr.len;
+        }
+      }
+      s_keys[tid] = keys;
+    }
+    __syncthreads();
+    if (tid < n_src) {
+      int cum = 0;
+      for (int i = 0; i < tid; ++i) cum += s_keys[i];
+      for (int r = beg; r < end; ++r) {
+        const int at = off + (r - beg);
+        if (at < kDecMaxRanges) {
+          r_cum[at] = cum;
+          cum += r_len[at];
+        }
+      }
+      if (tid == n_src - 1) {
+        const int n = min(off + (end - beg), kDecMaxRanges);
+        r_cum[n] = cum;
+        s_nr = n;
+      }
+    }
   }
   __syncthreads();
   const int nr = s_nr;
@@ -91,19 +139,6 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(PlanDev pd, DecodeD
     if (tid < LPK) st16(dk + sub * EV, ld16(kn));
     else if (tid < 2 * LPK) st16(dv + sub * EV, ld16(vn));
     if (g == 0 && tid == 0 && a.pos_resp && a.new_pos) a.pos_resp[(int64_t)b * a.resp_capacity + len_b] = a.new_pos[b];
-  }
-
-  // query chunk of this lane for each head, pre-scaled so that scores are in log2 units
-  float qf[GC][EV];
-  float slope2[GC];
-  const float pos_q = (bias && a.new_pos) ? a.new_pos[b] : 0.f;
-#pragma unroll
-  for (int c = 0; c < GC; ++c) {
-    const T *qp = static_cast<const T *>(a.q_new) + ((int64_t)b * Hq + head0 + c) * D + sub * EV;
-    Elem<T>::unpack(ld16(qp), qf[c]);
-#pragma unroll
-    for (int e = 0; e < EV; ++e) qf[c][e] *= a.scale * kLog2e;
-    slope2[c] = bias ? pd.slopes[head0 + c] * kLog2e : 0.f;
   }
 
   float m[GC], l[GC], acc[GC][EV];
