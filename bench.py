@@ -138,6 +138,8 @@ def main():
     ap.add_argument("--workload", default="c2_mha7b_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode-c5", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the prefill-only legs on the ragged and the grouped-query workloads")
     ap.add_argument("--no-online-prefill", action="store_true",
                     help="skip the path-cached (query rows only) prefill leg, e.g. so that a kernel trace of this "
                          "run holds full prefill launches only")
@@ -260,11 +262,57 @@ def main():
 
     if not args.no_online_prefill:
         out["prefill_online_cached"] = _bench_online_prefill(ctx, torch, B, wl, sets, scale)
+    if not args.no_other_workloads:
+        out["prefill_other_workloads"] = {
+            "c3_ragged_bf16": _bench_prefill_leg(ctx, torch, B, "c3_ragged_bf16", bias=False),
+            "c3_ragged_bf16+equilibrium_bias": _bench_prefill_leg(ctx, torch, B, "c3_ragged_bf16", bias=True),
+            "c4_gqa_bf16": _bench_prefill_leg(ctx, torch, B, "c4_gqa_bf16", bias=False),
+        }
     if not args.no_decode_c5:
         out["decode_c5"] = _bench_decode_c5(ctx, torch, B)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline(wl)
     print(json.dumps(out))
+
+
+def _bench_prefill_leg(ctx, torch, B, name, bias, reps=12):
+    """Prefill only, on another workload; with bias = True the tokens carry equilibrium positions
+    (Sec. 3.2.2 Eq. 1, from the library's host helper) and every head a linear distance penalty."""
+    wl = sp_synth.WORKLOADS[name]
+    sets, plans = [], []
+    for i in range(2):
+        seed = wl.seed + 17 * i
+        g = torch.Generator(device="cuda"); g.manual_seed(seed)
+        st = sp_synth.forkjoin_segtable(wl.preamble_len, sp_synth.draw_doc_lens(wl, np.random.default_rng(seed)),
+                                        wl.query_len)
+        rn = lambda h: torch.randn((st.n_tokens, h, wl.head_dim), generator=g, device="cuda").to(torch.bfloat16)
+        Q, K, V = rn(wl.n_q_heads), rn(wl.n_kv_heads), rn(wl.n_kv_heads)
+        sets.append((Q, K, V, torch.empty_like(Q)))
+        pos = slopes = None
+        if bias:
+            pos = B.equilibrium_positions(st.prompt_seg_off, st.seg_tok_start, st.seg_tok_len, st.seg_parent,
+                                          st.seg_path, st.n_tokens)
+            slopes = sp_synth.geometric_slopes(wl.n_q_heads)
+        plans.append(B.Plan(ctx, st.prompt_seg_off, st.seg_tok_start, st.seg_tok_len, st.seg_parent, st.seg_path,
+                            st.n_tokens, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, B.SP_BF16, tok_pos=pos,
+                            alibi_slopes=slopes))
+    scale = 1 / math.sqrt(wl.head_dim)
+    for i in range(4):
+        ctx.sp_forkjoin_prefill(plans[i % 2], *sets[i % 2], scale)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+    ev[0].record()
+    for i in range(reps):
+        ctx.sp_forkjoin_prefill(plans[i % 2], *sets[i % 2], scale)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(reps)]))
+    flops = float(np.mean([prefill_flops(p.visible_pairs(), wl.n_q_heads, wl.head_dim) for p in plans]))
+    by = float(np.mean([prefill_bytes(s[0].shape[0], wl.n_q_heads, wl.n_kv_heads, wl.head_dim, 2) for s in sets]))
+    return {"avg_launch_ms": round(ms, 4), "tflops": round(flops / (ms * 1e-3) / 1e12, 2),
+            "hbm_GBps": round(by / (ms * 1e-3) / 1e9, 1), "hbm_frac": round(by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "mfma_frac": round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "tokens": int(sets[0][0].shape[0]), "n_prompts": wl.n_prompts}
 
 
 def _bench_online_prefill(ctx, torch, B, wl, sets, scale, reps=20):
