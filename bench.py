@@ -138,6 +138,8 @@ def main():
     ap.add_argument("--workload", default="c2_mha7b_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode-c5", action="store_true")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="skip the leg that replays the whole step from a captured HIP graph")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="skip the prefill-only legs on the ragged and the grouped-query workloads")
     ap.add_argument("--no-online-prefill", action="store_true",
@@ -260,6 +262,26 @@ def main():
         except Exception:
             pass
 
+    if not args.no_graph:
+        # the same step, captured once per input set into a HIP graph and replayed (launch overhead of
+        # the nine kernels of a step leaves the host)
+        graphs = []
+        for j in range(2):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                ctx.sp_set_stream(torch.cuda.current_stream().cuda_stream)
+                step(j)
+            graphs.append(g)
+        ctx.sp_set_stream(torch.cuda.current_stream().cuda_stream)
+        for j in range(4):
+            graphs[j % 2].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for j in range(args.steps):
+            graphs[j % 2].replay()
+        torch.cuda.synchronize()
+        out["graph_replay"] = {"ms_per_step": round((time.perf_counter() - t0) / args.steps * 1e3, 4),
+                               "eager_ms_per_step": out["ms_per_step"]}
     if not args.no_online_prefill:
         out["prefill_online_cached"] = _bench_online_prefill(ctx, torch, B, wl, sets, scale)
     if not args.no_other_workloads:
