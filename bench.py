@@ -292,6 +292,8 @@ def main():
         }
     if not args.no_decode_c5:
         out["decode_c5"] = _bench_decode_c5(ctx, torch, B)
+        if not args.no_other_workloads:
+            out["decode_c5+equilibrium_bias"] = _bench_decode_c5(ctx, torch, B, steps=64, reps=3, bias=True)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline(wl)
     print(json.dumps(out))
@@ -370,8 +372,9 @@ def _bench_online_prefill(ctx, torch, B, wl, sets, scale, reps=20):
             "tflops": round(flops / (ms * 1e-3) / 1e12, 2)}
 
 
-def _bench_decode_c5(ctx, torch, B, steps=None, reps=5):
-    """Long pruned decode: 64 prompts, 2 of 20 paths kept, 256 steps over the growing cache."""
+def _bench_decode_c5(ctx, torch, B, steps=None, reps=5, bias=False):
+    """Long pruned decode: 64 prompts, 2 of 20 paths kept, 256 steps over the growing cache.
+    With bias = True the cache carries equilibrium positions and every head a distance penalty."""
     wl = sp_synth.WORKLOADS["c5_decode_bf16"]
     st = sp_synth.forkjoin_segtable(wl.preamble_len, [[wl.doc_len] * wl.n_paths] * wl.n_prompts, wl.query_len)
     g = torch.Generator(device="cuda"); g.manual_seed(wl.seed)
@@ -381,15 +384,25 @@ def _bench_decode_c5(ctx, torch, B, steps=None, reps=5):
     dq, dk, dv = rn(S, Bn, H, d), rn(S, Bn, H, d), rn(S, Bn, H, d)
     rng = np.random.default_rng(wl.seed)
     kept = torch.from_numpy(np.stack([rng.permutation(wl.n_paths)[:wl.top_k] for _ in range(Bn)]).astype(np.int32)).cuda()
+    pos = slopes = pos_resp = None
+    new_pos = [None] * S
+    if bias:
+        pos = B.equilibrium_positions(st.prompt_seg_off, st.seg_tok_start, st.seg_tok_len, st.seg_parent, st.seg_path,
+                                      st.n_tokens)
+        slopes = sp_synth.geometric_slopes(H)
+        pos_resp = torch.zeros((Bn, S), device="cuda")
+        p0 = float(pos.max()) + 1.0
+        new_pos = [torch.full((Bn,), p0 + s, device="cuda") for s in range(S)]
     plan = B.Plan(ctx, st.prompt_seg_off, st.seg_tok_start, st.seg_tok_len, st.seg_parent, st.seg_path, st.n_tokens,
-                  H, H, d, B.SP_BF16)
+                  H, H, d, B.SP_BF16, tok_pos=pos, alibi_slopes=slopes)
     Kr = torch.zeros((Bn, S, H, d), dtype=torch.bfloat16, device="cuda"); Vr = torch.zeros_like(Kr)
     o = torch.empty((S, Bn, H, d), dtype=torch.bfloat16, device="cuda")
     scale = 1 / math.sqrt(d)
 
     def loop():
         for s in range(S):
-            ctx.sp_pruned_decode(plan, kept, wl.top_k, K, V, Kr, Vr, S, dq[s], dk[s], dv[s], o[s], scale, resp_len_add=s)
+            ctx.sp_pruned_decode(plan, kept, wl.top_k, K, V, Kr, Vr, S, dq[s], dk[s], dv[s], o[s], scale, resp_len_add=s,
+                                 pos_resp=pos_resp, new_pos=new_pos[s])
 
     loop()
     torch.cuda.synchronize()
