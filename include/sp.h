@@ -18,6 +18,10 @@
  *   bit-identical outputs.  Supported: head_dim 64 or 128; dtype fp32 or bf16 (storage of
  *   Q/K/V/O and logits; all arithmetic accumulates in fp32); n_q_heads a multiple of
  *   n_kv_heads (query head h reads KV head h / (n_q_heads / n_kv_heads)).
+ *   Threads: a context (and the plans made on it) is used by one host thread at a time;
+ *   different contexts are independent.  The launching calls only enqueue kernels (no memsets;
+ *   sp_path_saliency allocates its workspace on first use or growth), so once warmed up they may
+ *   be captured into a HIP graph on the context's stream.
  */
 #ifndef SP_H_
 #define SP_H_
