@@ -132,9 +132,10 @@ int64_t sp_plan_joined_keys(const sp_plan *plan, int32_t prompt, const int32_t *
  * alias an input; rows of tokens not covered by any segment, and rows of segments flagged
  * seg_cached, are left untouched.
  * Layout limits (SP_ERR_UNSUPPORTED / SP_ERR_INVALID_ARG otherwise): base pointers 16-byte
- * aligned; strides multiples of 16 bytes (8 bf16 or 4 fp32 elements); head stride >= head_dim and
- * token stride >= head stride (token-major layouts); token strides below 2^26 elements;
- * softmax_scale positive and finite.
+ * aligned; strides multiples of 16 bytes (8 bf16 or 4 fp32 elements); all strides >= head_dim;
+ * Q and O token-major (token stride >= head stride); K and V token-major or head-major (a KV
+ * cache stored per head: head stride >= n_tokens * token stride), head stride below 2^31
+ * elements; token strides below 2^26 elements; softmax_scale positive and finite.
  */
 sp_status sp_forkjoin_prefill(sp_ctx *ctx, const sp_plan *plan, const void *Q, const void *K, const void *V,
                               void *O, int64_t q_tok_stride, int64_t q_head_stride, int64_t kv_tok_stride,

@@ -526,11 +526,13 @@ extern "C" sp_status sp_forkjoin_prefill(sp_ctx *ctx, const sp_plan *plan, const
   if (plan->ctx != ctx) return fail(&ctx->err, SP_ERR_INVALID_ARG, "plan was not created on this context");
   if (O == Q || O == K || O == V) return fail(&ctx->err, SP_ERR_INVALID_ARG, "O must not alias an input");
   const int64_t d = plan->head_dim;
-  if (q_head_stride < d || kv_head_stride < d || q_tok_stride < q_head_stride * 1 || kv_tok_stride < kv_head_stride * 1 ||
-      q_tok_stride < d || kv_tok_stride < d)
-    return fail(&ctx->err, SP_ERR_INVALID_ARG, "strides smaller than head_dim");
+  // Q and O are token-major; K and V may be token-major or head-major (a KV cache kept per head)
+  if (q_head_stride < d || kv_head_stride < d || q_tok_stride < q_head_stride || q_tok_stride < d || kv_tok_stride < d)
+    return fail(&ctx->err, SP_ERR_INVALID_ARG, "strides smaller than head_dim, or Q/O not token-major");
   if (q_tok_stride >= (int64_t(1) << 26) || kv_tok_stride >= (int64_t(1) << 26))
     return fail(&ctx->err, SP_ERR_UNSUPPORTED, "token strides must be below 2^26 elements");
+  if (kv_head_stride >= (int64_t(1) << 31))
+    return fail(&ctx->err, SP_ERR_UNSUPPORTED, "K/V head stride must be below 2^31 elements");
   const int64_t align = plan->dtype == SP_BF16 ? 8 : 4;   // 16-byte vector loads
   if (q_tok_stride % align || q_head_stride % align || kv_tok_stride % align || kv_head_stride % align)
     return fail(&ctx->err, SP_ERR_UNSUPPORTED, "strides must be multiples of %lld elements", (long long)align);

@@ -180,6 +180,28 @@ def test_independence_of_paths_is_bitwise(ctx):
     assert np.array_equal(base[others], pert[others])
 
 
+@pytest.mark.parametrize("dtype,Hq,Hkv", [("bf16", 4, 4), ("bf16", 8, 2), ("f32", 4, 2)])
+def test_head_major_kv_cache_layout(ctx, dtype, Hq, Hkv):
+    """K and V stored per head ([n_kv_heads, n_tokens, d], passed as strided [n_tokens, n_kv_heads, d]
+    views) give bit for bit what the token-major tensors give, and that matches the oracle."""
+    rng = np.random.default_rng(11)
+    st = sp_synth.forkjoin_segtable(40, [[100, 64, 77], [33, 128]], 24)
+    q, k, v = _rand(rng, st.n_tokens, Hq, Hkv, 128, dtype)
+    scale = 1 / math.sqrt(128)
+    base, plan = run_prefill(ctx, st, q, k, v, dtype)
+    check_attn(base, _oracle(st, q, k, v, scale), dtype, "token-major")
+    Q, K, V = dev(q, dtype), dev(k, dtype), dev(v, dtype)
+    Kh = K.transpose(0, 1).contiguous().transpose(0, 1)
+    Vh = V.transpose(0, 1).contiguous().transpose(0, 1)
+    assert Kh.stride(1) > Kh.stride(0) and torch.equal(Kh, K)
+    O = torch.full_like(Q, float("nan"))
+    ctx.sp_forkjoin_prefill(plan, Q, Kh, Vh, O, scale)
+    torch.cuda.synchronize()
+    got = O.float().cpu().numpy()
+    cov = covered_tokens(st)
+    assert np.array_equal(got[cov], base[cov])
+
+
 FULL = ["c2_mha7b_bf16", "c3_ragged_bf16", "c4_gqa_bf16"]
 
 
