@@ -60,6 +60,13 @@ __device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory", "m0");
 }
 
+// The same with the address split into a wave-uniform base (scalar registers) and a 32-bit per-lane
+// byte offset: no vector arithmetic per instruction and no 64-bit per-lane pointers to keep alive.
+__device__ __forceinline__ void dma16s(const void *sbase, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase)
+               : "memory", "m0");
+}
+
 template <int D, int HPW, int NW, bool BIAS>
 __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, const __bf16 *__restrict__ Q,
                                                                   const __bf16 *__restrict__ K,
@@ -161,7 +168,7 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
         const uint64_t o0 = (uint64_t)(uint32_t)(w.tok_start + w.row0 + tb) * q_ts * 2 + hoff;
 #pragma unroll
         for (int m = 0; m < NDMA; ++m)
-          dma16(Qb + (o0 + (uint64_t)(RG * m) * q_ts * 2) + (q_row_off + xq(m)), lds + m * (RG * ROWB));
+          dma16s(Qb + (o0 + (uint64_t)(RG * m) * q_ts * 2), q_row_off + xq(m), lds + m * (RG * ROWB));
       } else {
 #pragma unroll
         for (int m = 0; m < NDMA; ++m) {
@@ -185,7 +192,7 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
         const uint64_t o0 = (uint64_t)(uint32_t)(tok0 + rbase) * kv_ts * 2 + hoff;
 #pragma unroll
         for (int m = 0; m < NDMA; ++m)
-          dma16(KVb + (o0 + (uint64_t)(RG * m) * kv_ts * 2) + (kv_row_off + xkv[m]), lds + m * (RG * ROWB));
+          dma16s(KVb + (o0 + (uint64_t)(RG * m) * kv_ts * 2), kv_row_off + xkv[m], lds + m * (RG * ROWB));
         if (BIAS && tid < BK) preg = pd.tok_pos[tok0 + tid];
       } else {
 #pragma unroll
