@@ -284,6 +284,8 @@ def main():
                                "eager_ms_per_step": out["ms_per_step"]}
     if not args.no_online_prefill:
         out["prefill_online_cached"] = _bench_online_prefill(ctx, torch, B, wl, sets, scale)
+    if not args.no_online_prefill:
+        out["prefill_iterative_round"] = _bench_iterative_round(ctx, torch, B, wl, sets, scale)
     if not args.no_other_workloads:
         out["prefill_other_workloads"] = {
             "c3_ragged_bf16": _bench_prefill_leg(ctx, torch, B, "c3_ragged_bf16", bias=False),
@@ -370,6 +372,61 @@ def _bench_online_prefill(ctx, torch, B, wl, sets, scale, reps=20):
             "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(gbs / HBM_PEAK_GBS, 4), "algorithmic_bytes": kvb + qob, "algorithmic_flops": flops,
             "tflops": round(flops / (ms * 1e-3) / 1e12, 2)}
+
+
+def _bench_iterative_round(ctx, torch, B, wl, sets, scale, chain=(3, 7, 11, 15), reps=12):
+    """A later round of iterative superposition (Sec. 4.1.2, App. B) on the same token pool: the
+    documents kept so far form a cached chain behind the preamble and the remaining documents, each
+    with its query copy, are superposed behind the chain's tail.  Their ancestors are several
+    separate token ranges (preamble, the chain's documents)."""
+    plans = []
+    for s in sets:
+        t = s["st"]
+        start, length, parent, path, cached, off = [], [], [], [], [], [0]
+        for b in range(t.n_prompts):
+            p0, p1 = int(t.path_off[b]), int(t.path_off[b + 1])
+            base = len(start)
+            ps = int(t.preamble_seg[b])
+            start.append(int(t.seg_tok_start[ps])); length.append(int(t.seg_tok_len[ps])); parent.append(-1)
+            path.append(-1); cached.append(1)
+            tail = base
+            for c in chain:
+                ds = int(t.doc_seg[p0 + c])
+                start.append(int(t.seg_tok_start[ds])); length.append(int(t.seg_tok_len[ds])); parent.append(tail)
+                path.append(-1); cached.append(1)
+                tail = len(start) - 1
+            j = 0
+            for i in range(p1 - p0):
+                if i in chain:
+                    continue
+                ds, qs = int(t.doc_seg[p0 + i]), int(t.query_seg[p0 + i])
+                start.append(int(t.seg_tok_start[ds])); length.append(int(t.seg_tok_len[ds])); parent.append(tail)
+                path.append(j); cached.append(0)
+                start.append(int(t.seg_tok_start[qs])); length.append(int(t.seg_tok_len[qs]))
+                parent.append(len(start) - 2); path.append(j); cached.append(0)
+                j += 1
+            off.append(len(start))
+        i32 = lambda a: np.asarray(a, np.int32)
+        plans.append(B.Plan(ctx, i32(off), i32(start), i32(length), i32(parent), i32(path), t.n_tokens,
+                            wl.n_q_heads, wl.n_kv_heads, wl.head_dim, B.SP_BF16,
+                            seg_cached=np.asarray(cached, np.uint8)))
+    for i in range(4):
+        d = sets[i % 2]
+        ctx.sp_forkjoin_prefill(plans[i % 2], d["Q"], d["K"], d["V"], d["O"], scale)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+    ev[0].record()
+    for i in range(reps):
+        d = sets[i % 2]
+        ctx.sp_forkjoin_prefill(plans[i % 2], d["Q"], d["K"], d["V"], d["O"], scale)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(reps)]))
+    flops = prefill_flops(plans[0].visible_pairs(), wl.n_q_heads, wl.head_dim)
+    return {"kernel": "prefill_bf16_kernel", "rows": "documents not yet kept and their query copies",
+            "chain_documents": len(chain), "avg_launch_ms": round(ms, 4), "algorithmic_flops": flops,
+            "tflops": round(flops / (ms * 1e-3) / 1e12, 2),
+            "mfma_frac": round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
 
 
 def _bench_decode_c5(ctx, torch, B, steps=None, reps=5, bias=False):

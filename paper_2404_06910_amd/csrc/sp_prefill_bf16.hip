@@ -34,6 +34,7 @@
 namespace sp {
 
 constexpr int kItemBatch = 32;     // work items staged in LDS at a time
+constexpr int kRangeCache = 8;     // ancestor ranges per item kept in LDS beside them
 #ifndef SP_PADK
 #define SP_PADK 8
 #endif
@@ -95,6 +96,7 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
   __shared__ __attribute__((aligned(1024))) unsigned char ring[2 * STAGEB];
   __shared__ float Ps[2][BK];
   __shared__ __attribute__((aligned(16))) WorkItem s_items[kItemBatch];
+  __shared__ KeyRange s_ranges[kItemBatch][kRangeCache];       // first ancestor ranges of each staged item
   auto fK = [](int row) { return (row / RPC) % CPR; };
   auto fV = [](int row) { return 4 * ((row / RPC) % (CPR / 4)); };
 
@@ -145,20 +147,21 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
     int tok_start, row0, n_rows, anc_keys, range_off, n_ranges, head0, kv_head, r0_start;
   };
   // virtual key -> packed token for item w
-  auto map_tok = [&](const Item &w, int vk) -> int {
+  auto map_tok = [&](const Item &w, int local, int vk) -> int {
     vk = min(vk, w.anc_keys + w.row0 + w.n_rows - 1);           // past the end: re-read the last key (masked)
     if (vk >= w.anc_keys) return w.tok_start + (vk - w.anc_keys);
     if (w.n_ranges == 1) return w.r0_start + vk;
     int tok = 0;
+    const bool in_lds = w.n_ranges <= kRangeCache;              // else read the plan's table
     for (int r = 0; r < w.n_ranges; ++r) {
-      const KeyRange kr = pd.ranges[w.range_off + r];
+      const KeyRange kr = in_lds ? s_ranges[local][r] : pd.ranges[w.range_off + r];
       if (vk >= 0 && vk < kr.len) tok = kr.tok_start + vk;
       vk -= kr.len;
     }
     return tok;
   };
   // issue this wave's DMA loads of stage st of item w (st = -1: the Q tile) into slot `slot`
-  auto issue = [&](const Item &w, int st, int slot) {
+  auto issue = [&](const Item &w, int local, int st, int slot) {
     const uint32_t lds = ring_base + slot * STAGEB + wave * (32 * ROWB);
     if (st < 0) {
       const int tb = 32 * (wave / HPW);                       // first tile row of this wave's Q rows
@@ -184,8 +187,20 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
       int tok0 = -1;
       if (vk0 >= w.anc_keys) {
         if (vk0 + BK <= w.anc_keys + w.row0 + w.n_rows) tok0 = w.tok_start + (vk0 - w.anc_keys);
-      } else if (w.n_ranges == 1 && vk0 + BK <= w.anc_keys) {
-        tok0 = w.r0_start + vk0;
+      } else if (vk0 + BK <= w.anc_keys) {
+        if (w.n_ranges == 1) {
+          tok0 = w.r0_start + vk0;
+        } else if (w.n_ranges <= kRangeCache) {
+          // several ancestor ranges (cached paths, chains of kept documents): find the one that
+          // holds the whole stage, if any, in the LDS copy of the ranges
+          int acc = 0;
+          for (int r = 0; r < w.n_ranges; ++r) {
+            const int2 kr = *reinterpret_cast<const int2 *>(&s_ranges[local][r]);
+            const int start = __builtin_amdgcn_readfirstlane(kr.x), len = __builtin_amdgcn_readfirstlane(kr.y);
+            if (vk0 >= acc && vk0 + BK <= acc + len) tok0 = start + (vk0 - acc);
+            acc += len;
+          }
+        }
       }
       const uint64_t hoff = (uint64_t)(uint32_t)w.kv_head * kv_hs * 2;
       if (tok0 >= 0) {
@@ -197,10 +212,10 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
       } else {
 #pragma unroll
         for (int m = 0; m < NDMA; ++m) {
-          const int tok = map_tok(w, vk0 + rbase + RG * m + drow);
+          const int tok = map_tok(w, local, vk0 + rbase + RG * m + drow);
           dma16(KVb + ((uint64_t)(uint32_t)tok * kv_ts * 2 + hoff + xkv[m]), lds + m * (RG * ROWB));
         }
-        if (BIAS && tid < BK) preg = pd.tok_pos[map_tok(w, vk0 + tid)];
+        if (BIAS && tid < BK) preg = pd.tok_pos[map_tok(w, local, vk0 + tid)];
       }
     }
   };
@@ -244,7 +259,13 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
     int st = -1;                       // current stage of the current item
     int buf = 0;
 
-    issue(cur, -1, 0);
+    issue(cur, 0, -1, 0);
+    // the items' ancestor ranges, fetched under the first Q tile (items with one range carry it)
+    for (int i = tid; i < (it_end - it) * kRangeCache; i += T) {
+      const int li = i / kRangeCache, r = i % kRangeCache;
+      const int n_rng = s_items[li].n_ranges;
+      if (n_rng > 1 && r < n_rng) s_ranges[li][r] = pd.ranges[s_items[li].range_off + r];
+    }
     land_and_sync(0);
 
     while (true) {
@@ -253,8 +274,8 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
       const bool last_stage = st + 1 >= n_stages(cur);
       const bool have_next = !last_stage || it + 1 < it_end;
       if (have_next) {
-        if (!last_stage) issue(cur, st + 1, buf ^ 1);
-        else issue(nxt, -1, buf ^ 1);
+        if (!last_stage) issue(cur, it - batch, st + 1, buf ^ 1);
+        else issue(nxt, it + 1 - batch, -1, buf ^ 1);
       }
       const unsigned char *sl = ringp + buf * STAGEB;
 
