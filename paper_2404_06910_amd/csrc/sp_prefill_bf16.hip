@@ -68,6 +68,18 @@ __device__ __forceinline__ void dma16s(const void *sbase, uint32_t voff, uint32_
                : "memory", "m0");
 }
 
+// One dword per lane, 64 consecutive dwords in LDS: the positions of a stage's keys.
+__device__ __forceinline__ void dma4(const void *gptr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_base), "v"(gptr) : "memory", "m0");
+}
+
+// A wave-uniform float through the scalar data path (a read; its counter is not the vector one).
+__device__ __forceinline__ float sload_f32(const float *p) {
+  float v;
+  asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(p) : "memory");
+  return v;
+}
+
 template <int D, int HPW, int NW, bool BIAS>
 __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, const __bf16 *__restrict__ Q,
                                                                   const __bf16 *__restrict__ K,
@@ -94,7 +106,8 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
   // on the global-address side, so that the row reads of K and Q (ds_read_b128, 16 consecutive rows,
   // same chunk) and the transpose reads of V (4 rows x 32 bytes per 16 lanes) spread over the banks.
   __shared__ __attribute__((aligned(1024))) unsigned char ring[2 * STAGEB];
-  __shared__ float Ps[2][BK];
+  __shared__ __attribute__((aligned(256))) float Ps[2][BK < 64 ? 64 : BK];   // key positions (bias); one 64-lane DMA each
+  __shared__ __attribute__((aligned(256))) float Pq[64];                     // positions of the rows of the Q tile in flight
   __shared__ __attribute__((aligned(16))) WorkItem s_items[kItemBatch];
   __shared__ KeyRange s_ranges[kItemBatch][kRangeCache];       // first ancestor ranges of each staged item
   auto fK = [](int row) { return (row / RPC) % CPR; };
@@ -140,7 +153,15 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
   const int tr_chlo = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1), tr_sub8 = (lane & 1) * 8;
   const int tr_f = fV(4 * half + tr_row);                     // the other rows differ by multiples of 8
 
-  float preg = 0.f;
+  // bias state: slope and position of the wave's query row.  The positions of a stage's keys and of
+  // a tile's rows travel by DMA like the rows themselves and the slope through the scalar path, so
+  // the stage loop holds no vector load that the compiler tracks: a wait of its own for such a load
+  // would also wait for the DMA of the next stage.
+  float slope2 = 0.f, pos_q = 0.f;
+  static_assert(32 * NW / HPW <= 64, "one DMA instruction carries the positions of a Q tile");
+  const uint32_t ps_base = (uint32_t)(size_t)(lds_byte *)&Ps[0][0];
+  const uint32_t pq_base = (uint32_t)(size_t)(lds_byte *)&Pq[0];
+  constexpr uint32_t kPsSlotB = sizeof(Ps) / 2;
 
   // a work item as the loop keeps it (all fields wave-uniform)
   struct Item {
@@ -152,11 +173,18 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
     if (vk >= w.anc_keys) return w.tok_start + (vk - w.anc_keys);
     if (w.n_ranges == 1) return w.r0_start + vk;
     int tok = 0;
-    const bool in_lds = w.n_ranges <= kRangeCache;              // else read the plan's table
-    for (int r = 0; r < w.n_ranges; ++r) {
-      const KeyRange kr = in_lds ? s_ranges[local][r] : pd.ranges[w.range_off + r];
-      if (vk >= 0 && vk < kr.len) tok = kr.tok_start + vk;
-      vk -= kr.len;
+    if (w.n_ranges <= kRangeCache) {                            // the LDS copy, else the plan's table
+      for (int r = 0; r < w.n_ranges; ++r) {
+        const int2 kr = *reinterpret_cast<const int2 *>(&s_ranges[local][r]);
+        if (vk >= 0 && vk < kr.y) tok = kr.x + vk;
+        vk -= kr.y;
+      }
+    } else {
+      for (int r = 0; r < w.n_ranges; ++r) {
+        const KeyRange kr = pd.ranges[w.range_off + r];
+        if (vk >= 0 && vk < kr.len) tok = kr.tok_start + vk;
+        vk -= kr.len;
+      }
     }
     return tok;
   };
@@ -166,6 +194,7 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
     if (st < 0) {
       const int tb = 32 * (wave / HPW);                       // first tile row of this wave's Q rows
       const uint64_t hoff = (uint64_t)(uint32_t)(w.head0 + wave % HPW) * q_hs * 2;
+      if (BIAS && wave == 0) dma4(pd.tok_pos + (w.tok_start + w.row0 + min(lane, w.n_rows - 1)), pq_base);
       if (w.n_rows == 32 * NW / HPW) {
         // full tile: consecutive tokens, everything but the lane's own offset is wave-uniform
         const uint64_t o0 = (uint64_t)(uint32_t)(w.tok_start + w.row0 + tb) * q_ts * 2 + hoff;
@@ -208,21 +237,21 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
 #pragma unroll
         for (int m = 0; m < NDMA; ++m)
           dma16s(KVb + (o0 + (uint64_t)(RG * m) * kv_ts * 2), kv_row_off + xkv[m], lds + m * (RG * ROWB));
-        if (BIAS && tid < BK) preg = pd.tok_pos[tok0 + tid];
+        if (BIAS && wave == 0) dma4(pd.tok_pos + (tok0 + min(lane, BK - 1)), ps_base + slot * kPsSlotB);
       } else {
 #pragma unroll
         for (int m = 0; m < NDMA; ++m) {
           const int tok = map_tok(w, local, vk0 + rbase + RG * m + drow);
           dma16(KVb + ((uint64_t)(uint32_t)tok * kv_ts * 2 + hoff + xkv[m]), lds + m * (RG * ROWB));
         }
-        if (BIAS && tid < BK) preg = pd.tok_pos[map_tok(w, local, vk0 + tid)];
+        if (BIAS && wave == 0)
+          dma4(pd.tok_pos + map_tok(w, local, vk0 + min(lane, BK - 1)), ps_base + slot * kPsSlotB);
       }
     }
   };
   // all loads of this wave have landed; then meet the other waves
   auto land_and_sync = [&](int slot) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    if (BIAS && tid < BK) Ps[slot][tid] = preg;
     __syncthreads();
   };
 
@@ -243,7 +272,7 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
 
   bf16x8 qf[NJ];
   f32x16 o[NC];
-  float m_run = kNegBig, l_run = 0.f, slope2 = 0.f, pos_q = 0.f;
+  float m_run = kNegBig, l_run = 0.f;
 
   for (int batch = 0; batch < n_mine; batch += kItemBatch) {
     int it = batch;
@@ -304,8 +333,8 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
         m_run = kNegBig;
         l_run = 0.f;
         if (BIAS) {
-          slope2 = pd.slopes[head] * kLog2e;
-          pos_q = pd.tok_pos[cur.tok_start + cur.row0 + my_row];
+          slope2 = sload_f32(pd.slopes + head) * kLog2e;
+          pos_q = Pq[my_row];
         }
       } else {
 #pragma unroll

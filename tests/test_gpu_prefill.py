@@ -53,6 +53,8 @@ SMALL = [
     ("bf16", 8, 1, 64, 3, [[40, 41, 42]], 9, "grouped", True),                            # GQA 8
     ("bf16", 3, 3, 128, 130, [[300]], 31, "interleaved", False),                          # one doc = causal, 461 rows
     ("bf16", 6, 2, 128, 20, [[45, 77]], 5, "interleaved", False),                         # GQA 3 (odd group)
+    ("bf16", 4, 4, 128, 40, [[100, 64, 77], [33, 128]], 24, "interleaved", True),         # ungrouped heads, bias
+    ("bf16", 4, 2, 128, 64, [[128, 31], [200]], 9, "grouped", True),                      # GQA 2, bias
     ("f32", 4, 2, 128, 33, [[47, 20], [64, 3, 9]], 6, "grouped", True),
     ("f32", 2, 2, 64, 1, [[1]], 1, "interleaved", False),                                 # degenerate: 3 tokens
 ]
