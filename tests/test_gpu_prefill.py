@@ -108,6 +108,45 @@ def test_general_tree_with_gaps_and_untouched_rows(ctx):
         assert np.all(got[np.isnan(ref)] == 7.0)            # uncovered tokens are left untouched
 
 
+@pytest.mark.parametrize("Hq,Hkv,d,n_chain,bias", [(4, 4, 128, 11, False), (8, 2, 128, 6, True), (2, 2, 64, 12, True),
+                                                   (4, 1, 128, 3, False)])
+def test_deep_chains_of_separate_ranges(ctx, Hq, Hkv, d, n_chain, bias):
+    """A leaf behind a chain of documents that lie apart in the token pool (the shape of a late round
+    of iterative superposition): its ancestors are n_chain + 1 separate token ranges, of lengths that
+    are not multiples of the key-stage size, so stages straddle ranges; more ranges than the kernel
+    keeps beside its work items are covered too."""
+    rng = np.random.default_rng(100 + n_chain)
+    lens = [int(x) for x in rng.integers(9, 70, n_chain)]
+    root_len, leaf_len, gap = 21, 83, 5
+    # pool: root, then the chain's documents in reverse order with unused tokens between them, then the leaf
+    start, tok = {}, root_len + gap
+    for i in reversed(range(n_chain)):
+        start[i] = tok; tok += lens[i] + gap
+    leaf_start = tok; T = tok + leaf_len
+    seg_start = [0] + [start[i] for i in range(n_chain)] + [leaf_start]
+    seg_len = [root_len] + lens + [leaf_len]
+    parent = [-1] + list(range(n_chain)) + [n_chain]
+    path = [-1] * (n_chain + 1) + [0]
+    i32 = lambda a: np.asarray(a, np.int32)
+    off = i32([0, len(seg_start)])
+    q, k, v = _rand(rng, T, Hq, Hkv, d, "bf16")
+    pos = slopes = None
+    if bias:
+        pos = rng.uniform(0, 300, T).astype(np.float32); slopes = sp_synth.geometric_slopes(Hq)
+    plan = B.Plan(ctx, off, i32(seg_start), i32(seg_len), i32(parent), i32(path), T, Hq, Hkv, d, B.SP_BF16,
+                  tok_pos=pos, alibi_slopes=slopes)
+    Q, K, V = dev(q, "bf16"), dev(k, "bf16"), dev(v, "bf16")
+    O = torch.full_like(Q, 7.0)
+    scale = 1 / math.sqrt(d)
+    ctx.sp_forkjoin_prefill(plan, Q, K, V, O, scale)
+    torch.cuda.synchronize()
+    got = O.float().cpu().numpy()
+    ref = orc.forkjoin_prefill(q, k, v, off, i32(seg_start), i32(seg_len), i32(parent), scale, tok_pos=pos,
+                               alibi_slopes=slopes)
+    check_attn(got, ref, "bf16", "chain of %d" % n_chain)
+    assert np.all(got[np.isnan(ref)] == 7.0)                # the gaps are left untouched
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_cached_segments_random_trees(ctx, dtype):
     # Sec. 3.3.1 / Alg. 2: cached segments serve as keys; their output rows are not produced
