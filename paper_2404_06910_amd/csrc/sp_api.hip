@@ -334,6 +334,17 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
         while (c < 8 && acc * 8 >= total * c) xcd_begin[c++] = i + 1;
       }
     }
+    // The workgroups that share a compute unit do not run equally fast: the instruction arbiter
+    // serves the oldest wave of a SIMD first, so a workgroup dispatched in a later round (slot
+    // index / workgroups per round; the dispatcher fills every compute unit once per round) takes
+    // 7-15 % longer for the same work (measured from per-workgroup end times, stable from launch
+    // to launch).  Its load is weighted accordingly, in thousandths, so that all rounds end together.
+    const int32_t rounds = 8 / p->waves_per_wg, per_round = std::max(1, xcd_wgs / rounds);
+    auto slowness = [&](int32_t slot) -> int64_t {
+      static const int64_t four[4] = {1000, 1085, 1085, 1125}, two[2] = {1000, 1150};
+      const int32_t r = std::min(slot / per_round, rounds - 1);
+      return rounds == 4 ? four[r] : rounds == 2 ? two[r] : 1000;
+    };
     std::vector<std::vector<int32_t>> mine(p->n_wg);
     for (int32_t x = 0; x < 8; ++x) {
       // (work so far, workgroup) min-heap; ties go to the lower workgroup
@@ -344,7 +355,7 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
         auto top = heap.top();
         heap.pop();
         mine[x * xcd_wgs + top.second].push_back(static_cast<int32_t>(i));
-        heap.push({top.first + cost(p->items[i]), top.second});
+        heap.push({top.first + cost(p->items[i]) * slowness(top.second), top.second});
       }
     }
     std::vector<sp::WorkItem> permuted;
