@@ -303,8 +303,10 @@ __global__ __launch_bounds__(64 * NW, 2) void prefill_bf16_kernel(PlanDev pd, co
       const bool last_stage = st + 1 >= n_stages(cur);
       const bool have_next = !last_stage || it + 1 < it_end;
       if (have_next) {
+        __builtin_amdgcn_s_setprio(2);                     // requests leave before another wave's arithmetic
         if (!last_stage) issue(cur, it - batch, st + 1, buf ^ 1);
         else issue(nxt, it + 1 - batch, -1, buf ^ 1);
+        __builtin_amdgcn_s_setprio(0);
       }
       const unsigned char *sl = ringp + buf * STAGEB;
 
