@@ -174,6 +174,52 @@ def test_cached_segments_random_trees(ctx, dtype):
         assert np.all(got[np.isnan(ref)] == 7.0)            # cached and uncovered rows are left untouched
 
 
+_SHAPES = [(2, 2, 128), (4, 2, 128), (8, 2, 128), (4, 1, 64), (6, 3, 64), (4, 4, 64), (8, 2, 64), (3, 1, 128)]
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_forests_long_segments(ctx, seed):
+    """Random forests with segments of 1..90 tokens scattered over the pool (so ancestors are several
+    separate ranges of arbitrary length), random cached flags, every head grouping, with and without
+    bias: all computed rows against the oracle, everything else untouched."""
+    from test_host_plan import _random_table
+    rng = np.random.default_rng(500 + seed)
+    t = _random_table(rng, 2 + seed % 2, scramble=seed % 3 != 0)
+    S = len(t["seg_parent"])
+    # stretch the segments: new lengths, token ranges handed out again in random order with gaps
+    lens = rng.integers(1, 91, S).astype(np.int32)
+    order = rng.permutation(S) if seed % 3 != 0 else np.arange(S)
+    start = np.zeros(S, np.int32); tok = int(rng.integers(0, 5))
+    for sgm in order:
+        start[sgm] = tok; tok += int(lens[sgm]) + int(rng.integers(0, 4))
+    T = tok + 3
+    Hq, Hkv, d = _SHAPES[seed % len(_SHAPES)]
+    bias = seed % 2 == 1
+    cached = (rng.random(S) < 0.3).astype(np.uint8) if seed % 4 >= 2 else None
+    q, k, v = _rand(rng, T, Hq, Hkv, d, "bf16")
+    pos = slopes = None
+    if bias:
+        pos = rng.uniform(0, 400, T).astype(np.float32); slopes = sp_synth.geometric_slopes(Hq)
+    print("case: forest seed", seed, "tokens", T, "segments", S, (Hq, Hkv, d), "bias", bias, flush=True)
+    plan = B.Plan(ctx, t["prompt_seg_off"], start, lens, t["seg_parent"], t["seg_path"], T, Hq, Hkv, d, B.SP_BF16,
+                  tok_pos=pos, alibi_slopes=slopes, seg_cached=cached)
+    Q, K, V = dev(q, "bf16"), dev(k, "bf16"), dev(v, "bf16")
+    O = torch.full_like(Q, 7.0)
+    scale = 1 / math.sqrt(d)
+    ctx.sp_forkjoin_prefill(plan, Q, K, V, O, scale)
+    torch.cuda.synchronize()
+    got = O.float().cpu().numpy()
+    ref = orc.forkjoin_prefill(q, k, v, t["prompt_seg_off"], start, lens, t["seg_parent"], scale, tok_pos=pos,
+                               alibi_slopes=slopes)
+    if cached is not None:
+        for sgm in range(S):
+            if cached[sgm]:
+                ref[start[sgm]:start[sgm] + lens[sgm]] = np.nan
+    if not np.isnan(ref).all():
+        check_attn(got, ref, "bf16", "forest %d" % seed)
+    assert np.all(got[np.isnan(ref)] == 7.0)
+
+
 @pytest.mark.parametrize("packing", ["interleaved", "grouped"])
 def test_split_phase_prefill_equals_one_pass(ctx, packing):
     """Path caching (Sec. 3.3.1): preamble and documents are processed ahead of time, the query
