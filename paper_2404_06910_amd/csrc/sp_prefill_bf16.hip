@@ -35,12 +35,6 @@ namespace sp {
 
 constexpr int kItemBatch = 32;     // work items staged in LDS at a time
 constexpr int kRangeCache = 8;     // ancestor ranges per item kept in LDS beside them
-#ifndef SP_PADK
-#define SP_PADK 8
-#endif
-#ifndef SP_PADV
-#define SP_PADV 8
-#endif
 typedef bf16x4 __attribute__((address_space(3))) lds_bf16x4;
 typedef unsigned char __attribute__((address_space(3))) lds_byte;
 
