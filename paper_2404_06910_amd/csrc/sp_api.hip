@@ -404,13 +404,20 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
     std::vector<float> pos, slopes;
     if (t->tok_pos) pos.assign(t->tok_pos, t->tok_pos + t->n_tokens);
     if (t->alibi_slopes) slopes.assign(t->alibi_slopes, t->alibi_slopes + n_q_heads);
+    auto describe = [&](int32_t beg, int32_t end) {
+      sp::RangeDesc d{beg, end, 0, 0};
+      if (end > beg) { d.tok_start = p->dec_ranges[beg].tok_start; d.len = p->dec_ranges[beg].len; }
+      return d;
+    };
+    std::vector<sp::RangeDesc> shared_desc(B), path_desc(p->n_slots);
+    for (int32_t b = 0; b < B; ++b) shared_desc[b] = describe(p->shared_rng_beg[b], p->shared_rng_end[b]);
+    for (int32_t q = 0; q < p->n_slots; ++q) path_desc[q] = describe(p->path_rng_beg[q], p->path_rng_end[q]);
     size_t off = 0;
     const size_t o_groups = blob_reserve(off, p->groups), o_ranges = blob_reserve(off, p->ranges),
                  o_items = blob_reserve(off, p->items), o_wgb = blob_reserve(off, p->wg_begin), o_tokg = blob_reserve(off, p->tok_group),
                  o_pos = blob_reserve(off, pos), o_slopes = blob_reserve(off, slopes),
-                 o_poff = blob_reserve(off, p->path_off), o_sb = blob_reserve(off, p->shared_rng_beg),
-                 o_se = blob_reserve(off, p->shared_rng_end), o_pb = blob_reserve(off, p->path_rng_beg),
-                 o_pe = blob_reserve(off, p->path_rng_end), o_dr = blob_reserve(off, p->dec_ranges);
+                 o_poff = blob_reserve(off, p->path_off), o_sd = blob_reserve(off, shared_desc),
+                 o_pd = blob_reserve(off, path_desc), o_dr = blob_reserve(off, p->dec_ranges);
     hipError_t e = hipSetDevice(ctx->device);
     if (e == hipSuccess) e = hipMalloc(&p->dev_blob, off + 256);
     if (e != hipSuccess) {
@@ -429,10 +436,8 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
     up(o_pos, pos.data(), pos.size() * 4);
     up(o_slopes, slopes.data(), slopes.size() * 4);
     up(o_poff, p->path_off.data(), p->path_off.size() * 4);
-    up(o_sb, p->shared_rng_beg.data(), p->shared_rng_beg.size() * 4);
-    up(o_se, p->shared_rng_end.data(), p->shared_rng_end.size() * 4);
-    up(o_pb, p->path_rng_beg.data(), p->path_rng_beg.size() * 4);
-    up(o_pe, p->path_rng_end.data(), p->path_rng_end.size() * 4);
+    up(o_sd, shared_desc.data(), shared_desc.size() * sizeof(sp::RangeDesc));
+    up(o_pd, path_desc.data(), path_desc.size() * sizeof(sp::RangeDesc));
     up(o_dr, p->dec_ranges.data(), p->dec_ranges.size() * sizeof(sp::KeyRange));
     if (e != hipSuccess) {
       (void)hipFree(p->dev_blob);
@@ -447,10 +452,8 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
     d.tok_pos = pos.empty() ? nullptr : reinterpret_cast<const float *>(base + o_pos);
     d.slopes = slopes.empty() ? nullptr : reinterpret_cast<const float *>(base + o_slopes);
     d.path_off = reinterpret_cast<const int32_t *>(base + o_poff);
-    d.shared_rng_beg = reinterpret_cast<const int32_t *>(base + o_sb);
-    d.shared_rng_end = reinterpret_cast<const int32_t *>(base + o_se);
-    d.path_rng_beg = reinterpret_cast<const int32_t *>(base + o_pb);
-    d.path_rng_end = reinterpret_cast<const int32_t *>(base + o_pe);
+    d.shared_desc = reinterpret_cast<const sp::RangeDesc *>(base + o_sd);
+    d.path_desc = reinterpret_cast<const sp::RangeDesc *>(base + o_pd);
     d.dec_ranges = reinterpret_cast<const sp::KeyRange *>(base + o_dr);
     d.n_items = static_cast<int32_t>(p->items.size());
     d.wg_begin = reinterpret_cast<const int32_t *>(base + o_wgb);

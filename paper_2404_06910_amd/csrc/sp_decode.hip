@@ -67,22 +67,19 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(PlanDev pd, DecodeD
 
   // The joined cache [shared ; kept path 0 ; ... ; kept path k-1] as a list of token ranges with
   // running key counts.  Source 0 is the shared part, source j >= 1 the (j-1)-th kept path; one
-  // thread per source follows the tables (kept -> path slot -> ranges), so the dependent loads of
+  // thread per source follows the tables (kept -> path slot descriptor, which carries the first range), so the dependent loads of
   // all sources run side by side; two small prefix sums through LDS put the ranges in order.
   {
     const int n_src = min(a.k + 1, kDecMaxRanges);
-    int beg = 0, end = 0;
+    RangeDesc src{0, 0, 0, 0};
     if (tid == 0) {
-      beg = pd.shared_rng_beg[b];
-      end = pd.shared_rng_end[b];
+      src = pd.shared_desc[b];
     } else if (tid < n_src) {
       const int p0 = pd.path_off[b], np = pd.path_off[b + 1] - p0;
       const int kp = a.kept[(int64_t)b * a.k + (tid - 1)];
-      if (kp >= 0 && kp < np) {
-        beg = pd.path_rng_beg[p0 + kp];
-        end = pd.path_rng_end[p0 + kp];
-      }
+      if (kp >= 0 && kp < np) src = pd.path_desc[p0 + kp];
     }
+    const int beg = src.beg, end = src.end;
     if (tid < n_src) s_cnt[tid] = end - beg;
     __syncthreads();
     int off = 0, keys = 0;
@@ -91,7 +88,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(PlanDev pd, DecodeD
       for (int r = beg; r < end; ++r) {
         const int at = off + (r - beg);
         if (at < kDecMaxRanges) {
-          const KeyRange kr = pd.dec_ranges[r];
+          const KeyRange kr = r == beg ? KeyRange{src.tok_start, src.len} : pd.dec_ranges[r];
           r_start[at] = kr.tok_start;
           r_len[at] = kr.len;
           keys += kr.len;

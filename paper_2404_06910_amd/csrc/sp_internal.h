@@ -31,6 +31,12 @@ struct KeyRange {
   int32_t len;
 };
 
+struct RangeDesc {
+  int32_t beg, end;    // decode ranges [beg, end) of dec_ranges
+  int32_t tok_start;   // copy of dec_ranges[beg] (0, 0 when beg == end)
+  int32_t len;
+};
+
 // One prefill work item: a tile of query rows of one row group, for one group of query heads.
 // Self-contained (one 32-byte scalar load), so a workgroup never chases pointers between items.
 struct WorkItem {
@@ -55,10 +61,10 @@ struct PlanDev {
   const float *slopes;           // [n_q_heads] or nullptr
   // decode tables
   const int32_t *path_off;       // [n_prompts+1]
-  const int32_t *shared_rng_beg; // [n_prompts] first/last+1 range of the shared segments
-  const int32_t *shared_rng_end; // [n_prompts]
-  const int32_t *path_rng_beg;   // [n_slots] first/last+1 range of each path slot
-  const int32_t *path_rng_end;   // [n_slots]
+  // first/last+1 decode range and a copy of the first range: one 16-byte read tells a source's
+  // ranges when there is only one (the usual case), without a further dependent read
+  const RangeDesc *shared_desc;  // [n_prompts] the shared segments of each prompt
+  const RangeDesc *path_desc;    // [n_slots] each path slot
   const KeyRange *dec_ranges;
   int32_t n_items;
   int32_t n_wg;
