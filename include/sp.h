@@ -19,9 +19,11 @@
  *   Q/K/V/O and logits; all arithmetic accumulates in fp32); n_q_heads a multiple of
  *   n_kv_heads (query head h reads KV head h / (n_q_heads / n_kv_heads)).
  *   Threads: a context (and the plans made on it) is used by one host thread at a time;
- *   different contexts are independent.  The launching calls only enqueue kernels (no memsets;
- *   sp_path_saliency allocates its workspace on first use or growth), so once warmed up they may
- *   be captured into a HIP graph on the context's stream.
+ *   different contexts are independent.  The launching calls only enqueue kernels (no memsets; the
+ *   saliency accumulators are allocated in sp_create for 16384 path slots, and a call that needs more
+ *   allocates a larger block once and keeps the old one until sp_destroy, so a captured graph never
+ *   names freed memory), so they may be captured into a HIP graph on the context's stream.
+ *   A plan keeps its context alive: sp_destroy may be called before sp_plan_destroy.
  */
 #ifndef SP_H_
 #define SP_H_
@@ -99,11 +101,31 @@ const char *sp_version(void);
 sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *table, int32_t n_q_heads, int32_t n_kv_heads,
                          int32_t head_dim, sp_dtype dtype, sp_plan **out);
 void sp_plan_destroy(sp_plan *plan);
+/* Rebuild `plan` in place for another table (same head counts, head_dim and dtype): the prompt DAG
+ * changes per request -- one table per query (Alg. 3), one per round of iterative superposition
+ * (Sec. 4.1.2) -- while the plan object, and its device block when the new tables fit, stay.  On any
+ * error the plan is unchanged.  Tables travel in one asynchronous copy from a pinned staging buffer
+ * on the context's stream (also in sp_plan_create), ordered behind the work already enqueued there;
+ * device blocks of destroyed plans are kept by the context and reused, so a steady request loop
+ * calls neither hipMalloc nor hipFree.  Not for use while the stream is being captured. */
+sp_status sp_plan_update(sp_plan *plan, const sp_segtable *table);
 
 /* info[0]=n_prompts [1]=n_segments [2]=n_tokens [3]=n_path_slots [4]=n_row_groups (runs of
  * segments fused for the query side) [5]=n_tiles [6]=n_work_items [7]=max ancestor ranges.
  * HOST out pointer. */
 sp_status sp_plan_info(const sp_plan *plan, int64_t info[8]);
+/* Host inspection of the prefill work list as the kernel walks it.  Item i is 8 int32:
+ * {first token of its row group, first row of the tile inside the group, rows in the tile, ancestor keys,
+ * index of its first ancestor range, number of ancestor ranges, first query head | KV head << 16, first
+ * token of ancestor range 0}; the rows see the ancestor ranges (sp_plan_key_ranges: pairs {first token,
+ * length}, root to leaf) completely and the rows of their own group causally.  Worker slot s (a wave or a
+ * workgroup, depending on the kernel the plan selected; sp_plan_work_slots of them) owns items
+ * [slot_begin[s], slot_begin[s+1]).  Each call writes at most cap entries and returns the full count, or a
+ * negative sp_status (slot_begin has sp_plan_work_slots() + 1 entries).  HOST pointers. */
+int64_t sp_plan_work_items(const sp_plan *plan, int32_t *items_out, int64_t cap_items, int32_t *slot_begin_out,
+                           int64_t cap_slots);
+int64_t sp_plan_key_ranges(const sp_plan *plan, int32_t *ranges_out, int64_t cap);
+int64_t sp_plan_work_slots(const sp_plan *plan);
 /* Visible (query token, key token) pairs per head over the rows that are computed (tokens of
  * cached segments are keys only), the unit of the prefill FLOP count
  * 4 * head_dim * n_q_heads * pairs. */
@@ -154,14 +176,14 @@ sp_status sp_forkjoin_prefill(sp_ctx *ctx, const sp_plan *plan, const void *Q, c
 sp_status sp_path_saliency(sp_ctx *ctx, const void *logits, sp_dtype dtype, int64_t n_rows, int64_t vocab,
                            int64_t row_stride, const int32_t *target, const int32_t *row_path,
                            const float *prior, int32_t n_path_slots, sp_saliency_mode mode, float *score);
-
 /* ---- a3: top-k pruning (Sec. 3.2.3; Alg. 3) -------------------------------------------- */
 /*
  * Per prompt b, the k local path indices with the largest score, in descending score order,
  * ties to the lower index (NaN ranks last).  score: DEVICE fp32; path_off: DEVICE int32
  * [n_prompts+1] CSR into score; kept: DEVICE int32 [n_prompts, k].  If a prompt has fewer than
- * k paths the remaining entries are -1.  n_paths_max (HOST value) bounds every prompt's path
- * count and sizes the launch; SP_ERR_UNSUPPORTED above 4096.
+ * k paths the remaining entries are -1.  n_paths_max (HOST value) sizes the launch's LDS copy of a
+ * prompt's scores (SP_ERR_UNSUPPORTED above 4096); a prompt with more paths than that is still ranked
+ * completely, from global memory, only slower.
  */
 sp_status sp_prune_topk(sp_ctx *ctx, const float *score, const int32_t *path_off, int32_t n_prompts,
                         int32_t n_paths_max, int32_t k, int32_t *kept);

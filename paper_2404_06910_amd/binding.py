@@ -55,8 +55,12 @@ def lib() -> C.CDLL:
         "sp_version": (C.c_char_p, []),
         "sp_plan_create": (C.c_int, [vp, C.POINTER(_SegTable), i32, i32, i32, C.c_int, C.POINTER(vp)]),
         "sp_plan_destroy": (None, [vp]),
+        "sp_plan_update": (C.c_int, [vp, C.POINTER(_SegTable)]),
         "sp_plan_info": (C.c_int, [vp, C.POINTER(i64)]),
         "sp_plan_visible_pairs": (i64, [vp]),
+        "sp_plan_work_items": (i64, [vp, vp, i64, vp, i64]),
+        "sp_plan_work_slots": (i64, [vp]),
+        "sp_plan_key_ranges": (i64, [vp, vp, i64]),
         "sp_plan_path_offsets": (C.c_int, [vp, vp]),
         "sp_plan_path_offsets_device": (vp, [vp]),
         "sp_plan_visible_keys": (i64, [vp, i32, vp, i64]),
@@ -160,10 +164,10 @@ class Context:
 
     # -- a2 ------------------------------------------------------------------------------
     def sp_path_saliency(self, logits, target, row_path, n_path_slots: int, score, prior=None,
-                         mode: int = SALIENCY_SUM):
+                         mode: int = SALIENCY_SUM, _entry: str = "sp_path_saliency"):
         if logits.dim() != 2 or logits.stride(1) != 1:
             raise ValueError("logits must be [rows, vocab] with unit inner stride")
-        self._check(lib().sp_path_saliency(self._h, _dev(logits, "logits"), _dtype_code(logits), logits.shape[0],
+        self._check(getattr(lib(), _entry)(self._h, _dev(logits, "logits"), _dtype_code(logits), logits.shape[0],
                                            logits.shape[1], logits.stride(0), _dev(target, "target"),
                                            _dev(row_path, "row_path"), _dev(prior, "prior"), int(n_path_slots),
                                            int(mode), _dev(score, "score")))
@@ -213,6 +217,17 @@ class Plan:
             raise SpError(st, lib().sp_last_error(ctx._h if ctx else None).decode())
         self.n_prompts = t.n_prompts
 
+    def update(self, prompt_seg_off, seg_tok_start, seg_tok_len, seg_parent, seg_path, n_tokens: int, tok_pos=None,
+               alibi_slopes=None, seg_cached=None):
+        """sp_plan_update: rebuild this plan in place for another segment table."""
+        t, keep = _make_table(prompt_seg_off, seg_tok_start, seg_tok_len, seg_parent, seg_path, n_tokens, tok_pos,
+                              alibi_slopes, seg_cached)
+        st = lib().sp_plan_update(self._h, C.byref(t))
+        del keep
+        if st != 0:
+            raise SpError(st, lib().sp_last_error(self.ctx._h if self.ctx else None).decode())
+        self.n_prompts = t.n_prompts
+
     def close(self):
         if getattr(self, "_h", None) and self._h.value:
             lib().sp_plan_destroy(self._h)
@@ -230,6 +245,22 @@ class Plan:
         names = ["n_prompts", "n_segments", "n_tokens", "n_path_slots", "n_row_groups", "n_tiles", "n_work_items",
                  "max_ranges"]
         return dict(zip(names, [int(x) for x in a]))
+
+    def work_items(self):
+        """sp_plan_work_items: (items [n, 8] int32, slot_begin [n_slots + 1] int32)."""
+        n = int(lib().sp_plan_work_items(self._h, None, 0, None, 0))
+        ns = int(lib().sp_plan_work_slots(self._h))
+        items = np.zeros((max(n, 1), 8), dtype=np.int32)
+        begin = np.zeros(ns + 1, dtype=np.int32)
+        lib().sp_plan_work_items(self._h, _np_ptr(items), n, _np_ptr(begin), ns + 1)
+        return items[:n], begin
+
+    def key_ranges(self) -> np.ndarray:
+        """sp_plan_key_ranges: [n, 2] int32 (first token, length)."""
+        n = int(lib().sp_plan_key_ranges(self._h, None, 0))
+        out = np.zeros((max(n, 1), 2), dtype=np.int32)
+        lib().sp_plan_key_ranges(self._h, _np_ptr(out), n)
+        return out[:n]
 
     def visible_pairs(self) -> int:
         return int(lib().sp_plan_visible_pairs(self._h))

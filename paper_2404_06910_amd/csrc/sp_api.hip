@@ -4,10 +4,10 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <numeric>
-#include <queue>
 
 #include "sp_internal.h"
 
@@ -120,6 +120,14 @@ extern "C" const char *sp_version(void) { return "sp-forkjoin 0.1 (gfx950)"; }
 
 extern "C" const char *sp_last_error(const sp_ctx *ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
 
+static void *alloc_sal(int32_t slots) {
+  void *p = nullptr;
+  const size_t bytes = 256 + sizeof(sp::SalSlot) * size_t(slots);
+  if (hipMalloc(&p, bytes) != hipSuccess) return nullptr;
+  if (hipMemset(p, 0, bytes) != hipSuccess) { (void)hipFree(p); return nullptr; }
+  return p;
+}
+
 extern "C" sp_status sp_create(sp_ctx **out, int device, void *hip_stream) {
   if (!out) return fail(nullptr, SP_ERR_INVALID_ARG, "out is NULL");
   *out = nullptr;
@@ -127,60 +135,151 @@ extern "C" sp_status sp_create(sp_ctx **out, int device, void *hip_stream) {
   hipError_t e = hipGetDeviceCount(&n);
   if (e != hipSuccess || n <= 0)
     return fail(nullptr, SP_ERR_HIP, "no usable HIP device (%s)", e == hipSuccess ? "count is 0" : hipGetErrorString(e));
-  if (device < 0 || device >= n) return fail(nullptr, SP_ERR_INVALID_ARG, "device %d out of range [0,%d)", device, n);
+  if (device < 0 || device >= n || device >= sp::kMaxDevices)
+    return fail(nullptr, SP_ERR_INVALID_ARG, "device %d out of range [0,%d)", device, std::min(n, sp::kMaxDevices));
   SP_HIP(nullptr, hipSetDevice(device));
   sp_ctx *c = new (std::nothrow) sp_ctx;
   if (!c) return fail(nullptr, SP_ERR_WORKSPACE, "out of host memory");
   c->device = device;
   c->stream = static_cast<hipStream_t>(hip_stream);
+  int cu = 0;
+  if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cu > 0) c->n_cu = cu;
+  // the saliency accumulators are allocated here, so that the hot call allocates nothing in the usual case
+  c->sal_slots = sp::kSalDefaultSlots;
+  c->sal = alloc_sal(c->sal_slots);
+  if (!c->sal || hipEventCreateWithFlags(&c->stage_ev, hipEventDisableTiming) != hipSuccess) {
+    if (c->sal) (void)hipFree(c->sal);
+    delete c;
+    return fail(nullptr, SP_ERR_WORKSPACE, "could not allocate the context's workspace");
+  }
   *out = c;
   return SP_OK;
 }
 
+static void ctx_unref(sp_ctx *ctx) {
+  if (--ctx->refs == 0) delete ctx;
+}
+
 extern "C" void sp_destroy(sp_ctx *ctx) {
-  if (!ctx) return;
-  if (ctx->ws) (void)hipFree(ctx->ws);
-  delete ctx;
+  if (!ctx || ctx->closed) return;
+  (void)hipSetDevice(ctx->device);
+  if (ctx->stage_busy) (void)hipEventSynchronize(ctx->stage_ev);
+  if (ctx->sal) (void)hipFree(ctx->sal);
+  for (void *p : ctx->retired) (void)hipFree(p);
+  for (auto &b : ctx->blob_pool) (void)hipFree(b.first);
+  if (ctx->stage) (void)hipHostFree(ctx->stage);
+  if (ctx->stage_ev) (void)hipEventDestroy(ctx->stage_ev);
+  ctx->sal = nullptr; ctx->stage = nullptr; ctx->stage_ev = nullptr;
+  ctx->retired.clear(); ctx->blob_pool.clear();
+  ctx->closed = true;
+  ctx_unref(ctx);
 }
 
 extern "C" sp_status sp_set_stream(sp_ctx *ctx, void *hip_stream) {
   if (!ctx) return fail(nullptr, SP_ERR_INVALID_ARG, "ctx is NULL");
+  // plan tables are uploaded on the stream that was current when the plan was made: let the last
+  // upload finish before work may be ordered on another stream
+  if (ctx->stage_busy && static_cast<hipStream_t>(hip_stream) != ctx->stream) {
+    SP_HIP(ctx, hipEventSynchronize(ctx->stage_ev));
+    ctx->stage_busy = false;
+  }
   ctx->stream = static_cast<hipStream_t>(hip_stream);
   return SP_OK;
 }
 
-static sp_status ensure_ws(sp_ctx *ctx, size_t bytes) {
-  if (ctx->ws_bytes >= bytes) return SP_OK;
-  if (ctx->ws) {
-    SP_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    (void)hipFree(ctx->ws);
-    ctx->ws = nullptr;
-    ctx->ws_bytes = 0;
-  }
-  const size_t want = std::max(bytes, size_t(1) << 20);
-  if (hipMalloc(reinterpret_cast<void **>(&ctx->ws), want) != hipSuccess)
-    return fail(&ctx->err, SP_ERR_WORKSPACE, "could not allocate %zu bytes of workspace", want);
-  ctx->ws_bytes = want;
+// Saliency accumulators for n_slots path slots.  A block that is too small is replaced and kept until
+// sp_destroy (a captured graph may still name it); nothing is ever freed inside a hot call.
+static sp_status ensure_sal(sp_ctx *ctx, int32_t n_slots) {
+  if (ctx->sal_slots >= n_slots) return SP_OK;
+  int32_t want = ctx->sal_slots;
+  while (want < n_slots) want *= 2;
+  void *p = alloc_sal(want);
+  if (!p) return fail(&ctx->err, SP_ERR_WORKSPACE, "could not allocate accumulators for %d path slots", n_slots);
+  ctx->retired.push_back(ctx->sal);
+  ctx->sal = p;
+  ctx->sal_slots = want;
   return SP_OK;
 }
 
 // ---------------------------------------------------------------------------------------
 // Plan
 // ---------------------------------------------------------------------------------------
-extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n_q_heads, int32_t n_kv_heads,
-                                    int32_t head_dim, sp_dtype dtype, sp_plan **out) {
+namespace {
+
+// Hand the items of an ordered work list to n_slots workers (n_slots a multiple of 8; worker s belongs
+// to XCD s / (n_slots / 8)).  The list is cut into 8 contiguous, cost-balanced ranges, one per XCD, and
+// inside a range the items go, in order, each to the worker with the least work so far (ties: the
+// worker that has waited longest) -- the schedule a shared queue would produce, decided here.  At any
+// moment an XCD therefore works on a window of consecutive items (the blocks of one path, the heads
+// and paths of one (prompt, KV head)), whose K/V rows it then finds in its own L2.  Costs are small
+// positive integers; the least-loaded worker comes out of a bucket queue keyed by load, O(1) per item.
+// Output: owner[i] = worker of item i, and begin[s] = first position of worker s's slice in the
+// permuted list (items of a worker keep their order).  slow_milli[r]: relative slowness, in thousandths,
+// of the workers of dispatch round r (worker index within its XCD / workers per round).
+void hand_out(const std::vector<int32_t> &cost, int32_t n_slots, const int32_t *slow_milli, int32_t rounds,
+              std::vector<int32_t> &owner, std::vector<int32_t> &begin) {
+  // loads are kept in units of 1/16 of a cost unit so that the per-round weights (thousandths) fit
+  const size_t n = cost.size();
+  const int32_t per_xcd = n_slots / 8, per_round = std::max(1, per_xcd / rounds);
+  int64_t total = 0;
+  int32_t max_cost = 1;
+  for (int32_t c : cost) { total += c; max_cost = std::max(max_cost, c); }
+  size_t xcd_begin[9];
+  std::fill(xcd_begin, xcd_begin + 9, n);
+  xcd_begin[0] = 0;
+  {
+    int64_t acc = 0;
+    int32_t c = 1;
+    for (size_t i = 0; i < n && c < 8; ++i) {
+      acc += cost[i];
+      while (c < 8 && acc * 8 >= total * c) xcd_begin[c++] = i + 1;
+    }
+  }
+  std::vector<int32_t> weight(per_xcd);
+  for (int32_t w = 0; w < per_xcd; ++w) weight[w] = (16 * slow_milli[std::min(w / per_round, rounds - 1)] + 500) / 1000;
+  const int32_t max_w = *std::max_element(weight.begin(), weight.end());
+  owner.resize(n);
+  begin.assign(n_slots + 1, 0);
+  std::vector<int32_t> next(per_xcd), head, tail;
+  for (int32_t x = 0; x < 8; ++x) {
+    int64_t range_cost = 0;
+    for (size_t i = xcd_begin[x]; i < xcd_begin[x + 1]; ++i) range_cost += cost[i];
+    const size_t n_buckets = size_t((range_cost / per_xcd + 2 * int64_t(max_cost) + 2) * max_w);
+    head.assign(n_buckets, -1);
+    tail.assign(n_buckets, -1);
+    for (int32_t w = 0; w < per_xcd; ++w) next[w] = w + 1 < per_xcd ? w + 1 : -1;   // all workers at load 0, in order
+    head[0] = 0;
+    tail[0] = per_xcd - 1;
+    size_t lo = 0;
+    for (size_t i = xcd_begin[x]; i < xcd_begin[x + 1]; ++i) {
+      while (head[lo] < 0) ++lo;
+      const int32_t w = head[lo];
+      head[lo] = next[w];
+      if (head[lo] < 0) tail[lo] = -1;
+      size_t to = lo + size_t(cost[i]) * size_t(weight[w]);
+      if (to >= n_buckets) to = n_buckets - 1;       // cannot happen: the least load never exceeds the mean
+      next[w] = -1;
+      if (tail[to] < 0) head[to] = w; else next[tail[to]] = w;
+      tail[to] = w;
+      owner[i] = x * per_xcd + w;
+      ++begin[owner[i] + 1];
+    }
+  }
+  for (int32_t g = 0; g < n_slots; ++g) begin[g + 1] += begin[g];
+}
+
+// Validation, row groups, work list and decode tables of a plan (host only).
+sp_status build_plan(sp_ctx *ctx, const sp_segtable *t, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                     sp_dtype dtype, sp_plan *p) {
   std::string *err = errslot(ctx);
-  if (!out) return fail(err, SP_ERR_INVALID_ARG, "out is NULL");
-  *out = nullptr;
   if (n_q_heads <= 0 || n_kv_heads <= 0) return fail(err, SP_ERR_INVALID_ARG, "head counts must be positive");
   if (n_q_heads % n_kv_heads) return fail(err, SP_ERR_UNSUPPORTED, "n_q_heads must be a multiple of n_kv_heads");
+  if (n_q_heads > 0xffff) return fail(err, SP_ERR_UNSUPPORTED, "more than 65535 query heads");
   if (head_dim != 64 && head_dim != 128) return fail(err, SP_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
   if (dtype != SP_F32 && dtype != SP_BF16) return fail(err, SP_ERR_INVALID_ARG, "unknown dtype");
   sp_status st = validate_table(t, n_q_heads, err);
   if (st != SP_OK) return st;
 
-  sp_plan *p = new (std::nothrow) sp_plan;
-  if (!p) return fail(err, SP_ERR_WORKSPACE, "out of host memory");
   p->ctx = ctx;
   p->n_prompts = t->n_prompts; p->n_segments = t->n_segments; p->n_tokens = t->n_tokens;
   p->n_q_heads = n_q_heads; p->n_kv_heads = n_kv_heads; p->head_dim = head_dim; p->dtype = dtype;
@@ -192,6 +291,8 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
   p->seg_path.assign(t->seg_path, t->seg_path + S);
   p->has_pos = t->tok_pos != nullptr;
   p->has_slopes = t->alibi_slopes != nullptr;
+  if (t->tok_pos) p->pos.assign(t->tok_pos, t->tok_pos + t->n_tokens);
+  if (t->alibi_slopes) p->slopes.assign(t->alibi_slopes, t->alibi_slopes + n_q_heads);
 
   // --- row groups: fuse a child that is packed right behind its parent into the parent's run
   std::vector<int32_t> group_of(S, -1), group_last;
@@ -231,11 +332,9 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
       }
       rg.n_ranges = static_cast<int32_t>(p->ranges.size()) - rg.range_off;
       rg.anc_keys = anc;
-      if (rg.n_ranges > sp::kMaxRanges) {
-        delete p;
+      if (rg.n_ranges > sp::kMaxRanges)
         return fail(err, SP_ERR_UNSUPPORTED, "segment %d has %d disjoint ancestor key ranges (limit %d)", s,
                     rg.n_ranges, sp::kMaxRanges);
-      }
       p->max_ranges = std::max(p->max_ranges, rg.n_ranges);
       group_of[s] = static_cast<int32_t>(p->groups.size());
       group_last.push_back(s);
@@ -255,117 +354,89 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
       p->visible_pairs += n * rg.anc_keys + (int64_t(iv.second) * (iv.second + 1) - int64_t(iv.first) * (iv.first + 1)) / 2;
     }
   }
-  // device copy of the token -> group map: tokens of cached segments produce no rows
-  p->tok_group_dev = p->tok_group;
-  for (int32_t s = 0; s < S; ++s)
-    if (is_cached(s))
-      std::fill(p->tok_group_dev.begin() + t->seg_tok_start[s],
-                p->tok_group_dev.begin() + t->seg_tok_start[s] + t->seg_tok_len[s], -1);
+  // device copy of the token -> group map: tokens of cached segments produce no rows (fp32 kernel only)
+  if (dtype == SP_F32) {
+    p->tok_group_dev = p->tok_group;
+    for (int32_t s = 0; s < S; ++s)
+      if (is_cached(s))
+        std::fill(p->tok_group_dev.begin() + t->seg_tok_start[s],
+                  p->tok_group_dev.begin() + t->seg_tok_start[s] + t->seg_tok_len[s], -1);
+  }
 
-  // --- prefill work list.  Query heads that share a KV head are stacked in one workgroup
-  // (4 waves for 4 heads, else 2 waves), each wave owning 32 token rows of one head.
   const int32_t G = n_q_heads / n_kv_heads;
+  const int n_cu = ctx ? ctx->n_cu : 256;
+  struct Tile { int32_t group, row0, n_rows; };
+  std::vector<Tile> tiles;                            // tiles of the current prompt
+  // A tile streams every key up to its last row, so the partial tile of an interval goes first, where
+  // that stream is shortest, and the full tiles end at the interval's end.
+  auto tiles_of_prompt = [&](size_t &g, int32_t b, int32_t tile_rows) {
+    tiles.clear();
+    for (; g < p->groups.size() && p->groups[g].prompt == b; ++g)
+      for (auto &iv : live_rows[g]) {
+        const int32_t rem = (iv.second - iv.first) % tile_rows;
+        if (rem) tiles.push_back({int32_t(g), iv.first, rem});
+        for (int32_t r = iv.first + rem; r < iv.second; r += tile_rows) tiles.push_back({int32_t(g), r, tile_rows});
+      }
+    p->n_tiles += static_cast<int32_t>(tiles.size());
+  };
+  auto make_item = [&](const Tile &tl, int32_t head0, int32_t kv_head) {
+    const sp::RowGroup &rg = p->groups[tl.group];
+    sp::WorkItem w{};
+    w.tok_start = rg.tok_start; w.row0 = tl.row0;
+    w.n_rows = tl.n_rows;
+    w.anc_keys = rg.anc_keys; w.range_off = rg.range_off; w.n_ranges = rg.n_ranges;
+    w.head0 = head0 | (kv_head << 16);
+    w.r0_start = rg.n_ranges > 0 ? p->ranges[rg.range_off].tok_start : 0;
+    return w;
+  };
+  // --- prefill work list.  Query heads that share a KV head are stacked in one workgroup (4 waves for
+  // 4 heads, else 2 waves), each wave owning 32 token rows of one head.
+  // Persistent workgroups, 8 waves per compute unit.  The work list (ordered prompt, head group, tile) is
+  // handed out by hand_out() above; cost of an item = LDS stages streamed: one for Q plus the K/V stages,
+  // plus the epilogue.  The workgroups that share a compute unit do not run equally fast: the instruction
+  // arbiter serves the oldest wave of a SIMD first, so a workgroup dispatched in a later round (slot index
+  // / workgroups per round; the dispatcher fills every compute unit once per round) takes 7-15 % longer for
+  // the same work (measured from per-workgroup end times, stable from launch to launch).  Its load is
+  // weighted accordingly so that all rounds end together.  Items are written straight to their place in
+  // the permuted list, so that every workgroup reads one contiguous slice.
   p->heads_per_wg = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
   p->waves_per_wg = p->heads_per_wg == 4 ? 4 : 2;
   p->tile_rows = 32 * (p->waves_per_wg / p->heads_per_wg);
   const int32_t n_hg = n_q_heads / p->heads_per_wg;
   {
+    std::vector<Tile> all_tiles;
+    std::vector<int32_t> prompt_tile_off(B + 1, 0);
     size_t g = 0;
-    struct Tile { int32_t group, row0, n_rows; };
-    std::vector<Tile> tiles;                          // tiles of the current prompt
     for (int32_t b = 0; b < B; ++b) {
-      tiles.clear();
-      for (; g < p->groups.size() && p->groups[g].prompt == b; ++g)
-        // A tile streams every key up to its last row, so the partial tile of an interval goes
-        // first, where that stream is shortest, and the full tiles end at the interval's end.
-        for (auto &iv : live_rows[g]) {
-          const int32_t rem = (iv.second - iv.first) % p->tile_rows;
-          if (rem) tiles.push_back({int32_t(g), iv.first, rem});
-          for (int32_t r = iv.first + rem; r < iv.second; r += p->tile_rows)
-            tiles.push_back({int32_t(g), r, p->tile_rows});
-        }
-      p->n_tiles += static_cast<int32_t>(tiles.size());
-      // Order: all tiles of one (prompt, head group) are adjacent, so workgroups that read the
-      // same K/V rows run close together in time and, after the XCD remap in the kernel, on
-      // the same L2.
-      for (int32_t hg = 0; hg < n_hg; ++hg)
-        for (auto &tl : tiles) {
-          const sp::RowGroup &rg = p->groups[tl.group];
-          sp::WorkItem w{};
-          w.tok_start = rg.tok_start; w.row0 = tl.row0;
-          w.n_rows = tl.n_rows;
-          w.anc_keys = rg.anc_keys; w.range_off = rg.range_off; w.n_ranges = rg.n_ranges;
-          w.head0 = (hg * p->heads_per_wg) | ((hg * p->heads_per_wg / G) << 16);
-          w.r0_start = rg.n_ranges > 0 ? p->ranges[rg.range_off].tok_start : 0;
-          p->items.push_back(w);
-        }
-    }
-  }
-  // Persistent workgroups, 8 waves per compute unit.  The work list (ordered prompt, head group,
-  // tile) is cut into 8 contiguous, cost-balanced ranges, one per XCD (cost = LDS stages streamed:
-  // one for Q plus the K/V stages, plus the epilogue).  Inside a range the items are handed out in
-  // order, each to the workgroup with the least work so far -- the schedule a shared queue would
-  // produce.  At any moment an XCD therefore works on a window of consecutive items (all tiles of a
-  // path, the paths of one (prompt, KV head)), so a K/V row fetched from HBM is found in that XCD's
-  // L2 by the other tiles that need it, and no workgroup ends much later than the others.
-  // The items are stored permuted so that every workgroup reads one contiguous slice.
-  {
-    int n_cu = 256;
-    if (ctx) {
-      hipDeviceProp_t prop;
-      if (hipGetDeviceProperties(&prop, ctx->device) == hipSuccess && prop.multiProcessorCount > 0)
-        n_cu = prop.multiProcessorCount;
+      tiles_of_prompt(g, b, p->tile_rows);
+      all_tiles.insert(all_tiles.end(), tiles.begin(), tiles.end());
+      prompt_tile_off[b + 1] = static_cast<int32_t>(all_tiles.size());
     }
     const int32_t stage_keys = 16 * p->waves_per_wg;
-    p->n_wg = (((8 / p->waves_per_wg) * n_cu + 7) / 8) * 8;
-    const int32_t xcd_wgs = p->n_wg / 8;
-    auto cost = [&](const sp::WorkItem &w) {
-      return int64_t(2 + (w.anc_keys + w.row0 + w.n_rows + stage_keys - 1) / stage_keys);
-    };
-    int64_t total = 0;
-    for (auto &w : p->items) total += cost(w);
-    std::vector<size_t> xcd_begin(9, p->items.size());
-    xcd_begin[0] = 0;
+    std::vector<int32_t> tile_cost(all_tiles.size());
+    for (size_t i = 0; i < all_tiles.size(); ++i) {
+      const sp::RowGroup &rg = p->groups[all_tiles[i].group];
+      tile_cost[i] = 2 + (rg.anc_keys + all_tiles[i].row0 + all_tiles[i].n_rows + stage_keys - 1) / stage_keys;
+    }
+    const size_t n_items = all_tiles.size() * size_t(n_hg);
+    std::vector<int32_t> cost(n_items), owner;
     {
-      int64_t acc = 0;
-      int32_t c = 1;
-      for (size_t i = 0; i < p->items.size() && c < 8; ++i) {
-        acc += cost(p->items[i]);
-        while (c < 8 && acc * 8 >= total * c) xcd_begin[c++] = i + 1;
-      }
+      size_t i = 0;
+      for (int32_t b = 0; b < B; ++b)
+        for (int32_t hg = 0; hg < n_hg; ++hg)
+          for (int32_t tl = prompt_tile_off[b]; tl < prompt_tile_off[b + 1]; ++tl) cost[i++] = tile_cost[tl];
     }
-    // The workgroups that share a compute unit do not run equally fast: the instruction arbiter
-    // serves the oldest wave of a SIMD first, so a workgroup dispatched in a later round (slot
-    // index / workgroups per round; the dispatcher fills every compute unit once per round) takes
-    // 7-15 % longer for the same work (measured from per-workgroup end times, stable from launch
-    // to launch).  Its load is weighted accordingly, in thousandths, so that all rounds end together.
-    const int32_t rounds = 8 / p->waves_per_wg, per_round = std::max(1, xcd_wgs / rounds);
-    auto slowness = [&](int32_t slot) -> int64_t {
-      static const int64_t four[4] = {1000, 1085, 1085, 1125}, two[2] = {1000, 1150};
-      const int32_t r = std::min(slot / per_round, rounds - 1);
-      return rounds == 4 ? four[r] : rounds == 2 ? two[r] : 1000;
-    };
-    std::vector<std::vector<int32_t>> mine(p->n_wg);
-    for (int32_t x = 0; x < 8; ++x) {
-      // (work so far, workgroup) min-heap; ties go to the lower workgroup
-      std::priority_queue<std::pair<int64_t, int32_t>, std::vector<std::pair<int64_t, int32_t>>,
-                          std::greater<std::pair<int64_t, int32_t>>> heap;
-      for (int32_t w = 0; w < xcd_wgs; ++w) heap.push({0, w});
-      for (size_t i = xcd_begin[x]; i < xcd_begin[x + 1]; ++i) {
-        auto top = heap.top();
-        heap.pop();
-        mine[x * xcd_wgs + top.second].push_back(static_cast<int32_t>(i));
-        heap.push({top.first + cost(p->items[i]) * slowness(top.second), top.second});
-      }
-    }
-    std::vector<sp::WorkItem> permuted;
-    permuted.reserve(p->items.size());
-    p->wg_begin.assign(p->n_wg + 1, 0);
-    for (int32_t g = 0; g < p->n_wg; ++g) {
-      for (int32_t i : mine[g]) permuted.push_back(p->items[i]);
-      p->wg_begin[g + 1] = static_cast<int32_t>(permuted.size());
-    }
-    p->items.swap(permuted);
+    p->n_wg = (((8 / p->waves_per_wg) * n_cu + 7) / 8) * 8;
+    const int32_t rounds = 8 / p->waves_per_wg;
+    static const int32_t four[4] = {1000, 1085, 1085, 1125}, two[2] = {1000, 1150}, one[1] = {1000};
+    hand_out(cost, p->n_wg, rounds == 4 ? four : rounds == 2 ? two : one, rounds, owner, p->wg_begin);
+    p->items.resize(n_items);
+    std::vector<int32_t> at(p->wg_begin.begin(), p->wg_begin.end() - 1);
+    size_t i = 0;
+    for (int32_t b = 0; b < B; ++b)
+      for (int32_t hg = 0; hg < n_hg; ++hg)
+        for (int32_t tl = prompt_tile_off[b]; tl < prompt_tile_off[b + 1]; ++tl)
+          p->items[at[owner[i++]]++] = make_item(all_tiles[tl], hg * p->heads_per_wg, hg * p->heads_per_wg / G);
   }
 
   // --- decode gather tables: shared ranges per prompt, ranges per path slot
@@ -381,103 +452,215 @@ extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n
   p->path_rng_beg.assign(p->n_slots, 0);
   p->path_rng_end.assign(p->n_slots, 0);
   p->path_max_ranges.assign(B, 0);
+  std::vector<std::vector<int32_t>> segs_of_path;
   for (int32_t b = 0; b < B; ++b) {
     const size_t first = p->dec_ranges.size();
-    for (int32_t s = t->prompt_seg_off[b]; s < t->prompt_seg_off[b + 1]; ++s)
+    const int32_t np = p->path_off[b + 1] - p->path_off[b];
+    segs_of_path.assign(np, {});
+    for (int32_t s = t->prompt_seg_off[b]; s < t->prompt_seg_off[b + 1]; ++s) {
       if (t->seg_path[s] < 0) push_range(p->dec_ranges, first, t->seg_tok_start[s], t->seg_tok_len[s]);
+      else segs_of_path[t->seg_path[s]].push_back(s);
+    }
     p->shared_rng_beg[b] = static_cast<int32_t>(first);
     p->shared_rng_end[b] = static_cast<int32_t>(p->dec_ranges.size());
-    const int32_t np = p->path_off[b + 1] - p->path_off[b];
     for (int32_t q = 0; q < np; ++q) {
       const size_t pf = p->dec_ranges.size();
-      for (int32_t s = t->prompt_seg_off[b]; s < t->prompt_seg_off[b + 1]; ++s)
-        if (t->seg_path[s] == q) push_range(p->dec_ranges, pf, t->seg_tok_start[s], t->seg_tok_len[s]);
+      for (int32_t s : segs_of_path[q]) push_range(p->dec_ranges, pf, t->seg_tok_start[s], t->seg_tok_len[s]);
       const int32_t slot = p->path_off[b] + q;
       p->path_rng_beg[slot] = static_cast<int32_t>(pf);
       p->path_rng_end[slot] = static_cast<int32_t>(p->dec_ranges.size());
       p->path_max_ranges[b] = std::max(p->path_max_ranges[b], int32_t(p->dec_ranges.size() - pf));
     }
   }
+  return SP_OK;
+}
 
-  // --- upload
-  if (ctx) {
-    std::vector<float> pos, slopes;
-    if (t->tok_pos) pos.assign(t->tok_pos, t->tok_pos + t->n_tokens);
-    if (t->alibi_slopes) slopes.assign(t->alibi_slopes, t->alibi_slopes + n_q_heads);
-    auto describe = [&](int32_t beg, int32_t end) {
-      sp::RangeDesc d{beg, end, 0, 0};
-      if (end > beg) { d.tok_start = p->dec_ranges[beg].tok_start; d.len = p->dec_ranges[beg].len; }
-      return d;
-    };
-    std::vector<sp::RangeDesc> shared_desc(B), path_desc(p->n_slots);
-    for (int32_t b = 0; b < B; ++b) shared_desc[b] = describe(p->shared_rng_beg[b], p->shared_rng_end[b]);
-    for (int32_t q = 0; q < p->n_slots; ++q) path_desc[q] = describe(p->path_rng_beg[q], p->path_rng_end[q]);
-    size_t off = 0;
-    const size_t o_groups = blob_reserve(off, p->groups), o_ranges = blob_reserve(off, p->ranges),
-                 o_items = blob_reserve(off, p->items), o_wgb = blob_reserve(off, p->wg_begin), o_tokg = blob_reserve(off, p->tok_group),
-                 o_pos = blob_reserve(off, pos), o_slopes = blob_reserve(off, slopes),
-                 o_poff = blob_reserve(off, p->path_off), o_sd = blob_reserve(off, shared_desc),
-                 o_pd = blob_reserve(off, path_desc), o_dr = blob_reserve(off, p->dec_ranges);
-    hipError_t e = hipSetDevice(ctx->device);
-    if (e == hipSuccess) e = hipMalloc(&p->dev_blob, off + 256);
-    if (e != hipSuccess) {
-      delete p;
-      return fail(err, SP_ERR_HIP, "plan upload: %s", hipGetErrorString(e));
+// Device copy of a plan's tables: every table is laid out in the context's pinned staging buffer and
+// leaves in ONE asynchronous copy on the context's stream, into a device block taken from the blocks
+// of destroyed plans when one is large enough (no hipMalloc / hipFree per request).  Work enqueued on
+// that stream afterwards finds the tables in place.
+sp_status upload_plan(sp_ctx *ctx, sp_plan *p, void *reuse_blob, size_t reuse_bytes) {
+  const int32_t B = p->n_prompts;
+  auto describe = [&](int32_t beg, int32_t end) {
+    sp::RangeDesc d{beg, end, 0, 0};
+    if (end > beg) { d.tok_start = p->dec_ranges[beg].tok_start; d.len = p->dec_ranges[beg].len; }
+    return d;
+  };
+  std::vector<sp::RangeDesc> shared_desc(B), path_desc(p->n_slots);
+  for (int32_t b = 0; b < B; ++b) shared_desc[b] = describe(p->shared_rng_beg[b], p->shared_rng_end[b]);
+  for (int32_t q = 0; q < p->n_slots; ++q) path_desc[q] = describe(p->path_rng_beg[q], p->path_rng_end[q]);
+  struct Piece { const void *src; size_t bytes, at; };
+  std::vector<Piece> pieces;
+  size_t off = 0;
+  auto add = [&](const void *src, size_t bytes) {
+    off = (off + 255) & ~size_t(255);
+    pieces.push_back({src, bytes, off});
+    off += bytes + 16;
+    return pieces.back().at;
+  };
+  const size_t o_groups = add(p->groups.data(), p->groups.size() * sizeof(sp::RowGroup)),
+               o_ranges = add(p->ranges.data(), p->ranges.size() * sizeof(sp::KeyRange)),
+               o_items = add(p->items.data(), p->items.size() * sizeof(sp::WorkItem)),
+               o_wgb = add(p->wg_begin.data(), p->wg_begin.size() * 4),
+               o_tokg = add(p->tok_group_dev.data(), p->tok_group_dev.size() * 4),
+               o_pos = add(p->pos.data(), p->pos.size() * 4), o_slopes = add(p->slopes.data(), p->slopes.size() * 4),
+               o_poff = add(p->path_off.data(), p->path_off.size() * 4),
+               o_sd = add(shared_desc.data(), shared_desc.size() * sizeof(sp::RangeDesc)),
+               o_pd = add(path_desc.data(), path_desc.size() * sizeof(sp::RangeDesc)),
+               o_dr = add(p->dec_ranges.data(), p->dec_ranges.size() * sizeof(sp::KeyRange));
+  const size_t total = off + 256;
+  SP_HIP(ctx, hipSetDevice(ctx->device));
+  // device block: the plan's own (an update), else the smallest pooled block that fits, else a new one
+  void *blob = nullptr;
+  size_t blob_bytes = 0;
+  if (reuse_blob && reuse_bytes >= total) {
+    blob = reuse_blob; blob_bytes = reuse_bytes;
+  } else {
+    int best = -1;
+    for (size_t i = 0; i < ctx->blob_pool.size(); ++i)
+      if (ctx->blob_pool[i].second >= total && (best < 0 || ctx->blob_pool[i].second < ctx->blob_pool[best].second))
+        best = int(i);
+    if (best >= 0) {
+      blob = ctx->blob_pool[best].first; blob_bytes = ctx->blob_pool[best].second;
+      ctx->blob_pool.erase(ctx->blob_pool.begin() + best);
+    } else {
+      blob_bytes = ((total + total / 4) + 65535) & ~size_t(65535);      // headroom: the next table may be larger
+      if (hipMalloc(&blob, blob_bytes) != hipSuccess)
+        return fail(&ctx->err, SP_ERR_WORKSPACE, "could not allocate %zu bytes for the plan's tables", blob_bytes);
     }
-    char *base = static_cast<char *>(p->dev_blob);
-    auto up = [&](size_t at, const void *src, size_t bytes) {
-      if (bytes && e == hipSuccess) e = hipMemcpy(base + at, src, bytes, hipMemcpyHostToDevice);
-    };
-    up(o_groups, p->groups.data(), p->groups.size() * sizeof(sp::RowGroup));
-    up(o_ranges, p->ranges.data(), p->ranges.size() * sizeof(sp::KeyRange));
-    up(o_items, p->items.data(), p->items.size() * sizeof(sp::WorkItem));
-    up(o_wgb, p->wg_begin.data(), p->wg_begin.size() * 4);
-    up(o_tokg, p->tok_group_dev.data(), p->tok_group_dev.size() * 4);
-    up(o_pos, pos.data(), pos.size() * 4);
-    up(o_slopes, slopes.data(), slopes.size() * 4);
-    up(o_poff, p->path_off.data(), p->path_off.size() * 4);
-    up(o_sd, shared_desc.data(), shared_desc.size() * sizeof(sp::RangeDesc));
-    up(o_pd, path_desc.data(), path_desc.size() * sizeof(sp::RangeDesc));
-    up(o_dr, p->dec_ranges.data(), p->dec_ranges.size() * sizeof(sp::KeyRange));
-    if (e != hipSuccess) {
-      (void)hipFree(p->dev_blob);
-      delete p;
-      return fail(err, SP_ERR_HIP, "plan upload: %s", hipGetErrorString(e));
-    }
-    sp::PlanDev &d = p->dev;
-    d.groups = reinterpret_cast<const sp::RowGroup *>(base + o_groups);
-    d.ranges = reinterpret_cast<const sp::KeyRange *>(base + o_ranges);
-    d.items = reinterpret_cast<const sp::WorkItem *>(base + o_items);
-    d.tok_group = reinterpret_cast<const int32_t *>(base + o_tokg);
-    d.tok_pos = pos.empty() ? nullptr : reinterpret_cast<const float *>(base + o_pos);
-    d.slopes = slopes.empty() ? nullptr : reinterpret_cast<const float *>(base + o_slopes);
-    d.path_off = reinterpret_cast<const int32_t *>(base + o_poff);
-    d.shared_desc = reinterpret_cast<const sp::RangeDesc *>(base + o_sd);
-    d.path_desc = reinterpret_cast<const sp::RangeDesc *>(base + o_pd);
-    d.dec_ranges = reinterpret_cast<const sp::KeyRange *>(base + o_dr);
-    d.n_items = static_cast<int32_t>(p->items.size());
-    d.wg_begin = reinterpret_cast<const int32_t *>(base + o_wgb);
-    d.n_wg = p->n_wg;
-    d.n_tokens = p->n_tokens;
-    d.n_prompts = p->n_prompts;
-    d.n_q_heads = n_q_heads; d.n_kv_heads = n_kv_heads; d.head_dim = head_dim;
   }
+  auto give_back = [&]() { if (blob != reuse_blob) ctx->blob_pool.push_back({blob, blob_bytes}); };
+  // staging buffer: wait until the previous upload has left it, grow if needed
+  if (ctx->stage_busy) {
+    hipError_t e = hipEventSynchronize(ctx->stage_ev);
+    if (e != hipSuccess) { give_back(); return fail(&ctx->err, SP_ERR_HIP, "plan upload: %s", hipGetErrorString(e)); }
+    ctx->stage_busy = false;
+  }
+  if (ctx->stage_bytes < total) {
+    if (ctx->stage) (void)hipHostFree(ctx->stage);
+    ctx->stage = nullptr;
+    ctx->stage_bytes = 0;
+    const size_t want = std::max(total + total / 4, size_t(1) << 20);
+    if (hipHostMalloc(&ctx->stage, want, hipHostMallocDefault) != hipSuccess) {
+      give_back();
+      return fail(&ctx->err, SP_ERR_WORKSPACE, "could not allocate %zu bytes of pinned staging memory", want);
+    }
+    ctx->stage_bytes = want;
+  }
+  char *stg = static_cast<char *>(ctx->stage);
+  for (auto &pc : pieces)
+    if (pc.bytes) std::memcpy(stg + pc.at, pc.src, pc.bytes);
+  hipError_t e = hipMemcpyAsync(blob, stg, total, hipMemcpyHostToDevice, ctx->stream);
+  if (e == hipSuccess) e = hipEventRecord(ctx->stage_ev, ctx->stream);
+  if (e != hipSuccess) { give_back(); return fail(&ctx->err, SP_ERR_HIP, "plan upload: %s", hipGetErrorString(e)); }
+  ctx->stage_busy = true;
+  if (p->dev_blob && p->dev_blob != blob) ctx->blob_pool.push_back({p->dev_blob, p->dev_blob_bytes});
+  p->dev_blob = blob;
+  p->dev_blob_bytes = blob_bytes;
+  char *base = static_cast<char *>(blob);
+  sp::PlanDev &d = p->dev;
+  d = sp::PlanDev{};
+  d.groups = reinterpret_cast<const sp::RowGroup *>(base + o_groups);
+  d.ranges = reinterpret_cast<const sp::KeyRange *>(base + o_ranges);
+  d.items = reinterpret_cast<const sp::WorkItem *>(base + o_items);
+  d.wg_begin = reinterpret_cast<const int32_t *>(base + o_wgb);
+  d.tok_group = reinterpret_cast<const int32_t *>(base + o_tokg);
+  d.tok_pos = p->pos.empty() ? nullptr : reinterpret_cast<const float *>(base + o_pos);
+  d.slopes = p->slopes.empty() ? nullptr : reinterpret_cast<const float *>(base + o_slopes);
+  d.path_off = reinterpret_cast<const int32_t *>(base + o_poff);
+  d.shared_desc = reinterpret_cast<const sp::RangeDesc *>(base + o_sd);
+  d.path_desc = reinterpret_cast<const sp::RangeDesc *>(base + o_pd);
+  d.dec_ranges = reinterpret_cast<const sp::KeyRange *>(base + o_dr);
+  d.n_items = static_cast<int32_t>(p->items.size());
+  d.n_wg = p->n_wg;
+  d.n_tokens = p->n_tokens;
+  d.n_prompts = p->n_prompts;
+  d.n_q_heads = p->n_q_heads; d.n_kv_heads = p->n_kv_heads; d.head_dim = p->head_dim;
+  return SP_OK;
+}
+
+}  // namespace
+
+extern "C" sp_status sp_plan_create(sp_ctx *ctx, const sp_segtable *t, int32_t n_q_heads, int32_t n_kv_heads,
+                                    int32_t head_dim, sp_dtype dtype, sp_plan **out) {
+  std::string *err = errslot(ctx);
+  if (!out) return fail(err, SP_ERR_INVALID_ARG, "out is NULL");
+  *out = nullptr;
+  if (ctx && ctx->closed) return fail(nullptr, SP_ERR_INVALID_ARG, "context was destroyed");
+  sp_plan *p = new (std::nothrow) sp_plan;
+  if (!p) return fail(err, SP_ERR_WORKSPACE, "out of host memory");
+  sp_status st = build_plan(ctx, t, n_q_heads, n_kv_heads, head_dim, dtype, p);
+  if (st == SP_OK && ctx) st = upload_plan(ctx, p, nullptr, 0);
+  if (st != SP_OK) { delete p; return st; }
+  if (ctx) ++ctx->refs;
   *out = p;
+  return SP_OK;
+}
+
+extern "C" sp_status sp_plan_update(sp_plan *plan, const sp_segtable *t) {
+  if (!plan) return fail(nullptr, SP_ERR_INVALID_ARG, "plan is NULL");
+  sp_ctx *ctx = plan->ctx;
+  if (ctx && ctx->closed) return fail(nullptr, SP_ERR_INVALID_ARG, "context was destroyed");
+  sp_plan fresh;
+  sp_status st = build_plan(ctx, t, plan->n_q_heads, plan->n_kv_heads, plan->head_dim, plan->dtype, &fresh);
+  if (st != SP_OK) return st;                         // the plan is unchanged
+  if (ctx) {
+    // The old tables may still be read by kernels in flight on the stream; the copy that replaces
+    // them is ordered behind those kernels on the same stream.
+    fresh.dev_blob = plan->dev_blob;
+    fresh.dev_blob_bytes = plan->dev_blob_bytes;
+    st = upload_plan(ctx, &fresh, plan->dev_blob, plan->dev_blob_bytes);
+    if (st != SP_OK) { fresh.dev_blob = nullptr; return st; }
+  }
+  *plan = std::move(fresh);
+  fresh.dev_blob = nullptr;
   return SP_OK;
 }
 
 extern "C" void sp_plan_destroy(sp_plan *plan) {
   if (!plan) return;
-  if (plan->dev_blob) (void)hipFree(plan->dev_blob);
+  sp_ctx *ctx = plan->ctx;
+  if (plan->dev_blob) {
+    // keep the block for the next plan of this context (work that still reads it is ordered before
+    // the next upload on the same stream); a closed context has nothing to keep it in
+    if (ctx && !ctx->closed && ctx->blob_pool.size() < 8) ctx->blob_pool.push_back({plan->dev_blob, plan->dev_blob_bytes});
+    else (void)hipFree(plan->dev_blob);
+  }
   delete plan;
+  if (ctx) ctx_unref(ctx);
 }
 
 extern "C" sp_status sp_plan_info(const sp_plan *p, int64_t info[8]) {
   if (!p || !info) return fail(nullptr, SP_ERR_INVALID_ARG, "NULL argument");
   info[0] = p->n_prompts; info[1] = p->n_segments; info[2] = p->n_tokens; info[3] = p->n_slots;
-  info[4] = int64_t(p->groups.size()); info[5] = p->n_tiles; info[6] = int64_t(p->items.size());
+  info[4] = int64_t(p->groups.size()); info[5] = p->n_tiles;
+  info[6] = int64_t(p->items.size());
   info[7] = p->max_ranges;
   return SP_OK;
+}
+
+extern "C" int64_t sp_plan_work_items(const sp_plan *p, int32_t *items_out, int64_t cap_items, int32_t *slot_begin_out,
+                                      int64_t cap_slots) {
+  if (!p || (cap_items > 0 && !items_out) || (cap_slots > 0 && !slot_begin_out)) return SP_ERR_INVALID_ARG;
+  const std::vector<sp::WorkItem> &it = p->items;
+  const std::vector<int32_t> &sb = p->wg_begin;
+  static_assert(sizeof(sp::WorkItem) == 8 * sizeof(int32_t), "an item is 8 int32");
+  const int64_t n = std::min<int64_t>(cap_items, int64_t(it.size()));
+  if (n > 0) std::memcpy(items_out, it.data(), size_t(n) * sizeof(sp::WorkItem));
+  for (int64_t i = 0; i < cap_slots && i < int64_t(sb.size()); ++i) slot_begin_out[i] = sb[i];
+  return int64_t(it.size());
+}
+
+extern "C" int64_t sp_plan_key_ranges(const sp_plan *p, int32_t *out, int64_t cap) {
+  if (!p || (cap > 0 && !out)) return SP_ERR_INVALID_ARG;
+  const int64_t n = std::min<int64_t>(cap, int64_t(p->ranges.size()));
+  if (n > 0) std::memcpy(out, p->ranges.data(), size_t(n) * sizeof(sp::KeyRange));
+  return int64_t(p->ranges.size());
+}
+
+extern "C" int64_t sp_plan_work_slots(const sp_plan *p) {
+  if (!p) return SP_ERR_INVALID_ARG;
+  return int64_t(p->wg_begin.size()) - 1;
 }
 
 extern "C" int64_t sp_plan_visible_pairs(const sp_plan *p) { return p ? p->visible_pairs : SP_ERR_INVALID_ARG; }
@@ -566,11 +749,9 @@ extern "C" sp_status sp_forkjoin_prefill(sp_ctx *ctx, const sp_plan *plan, const
 // ---------------------------------------------------------------------------------------
 // a2 saliency
 // ---------------------------------------------------------------------------------------
-extern "C" sp_status sp_path_saliency(sp_ctx *ctx, const void *logits, sp_dtype dtype, int64_t n_rows,
-                                      int64_t vocab, int64_t row_stride, const int32_t *target,
-                                      const int32_t *row_path, const float *prior, int32_t n_path_slots,
-                                      sp_saliency_mode mode, float *score) {
-  if (!ctx) return fail(nullptr, SP_ERR_INVALID_ARG, "ctx is NULL");
+static sp_status check_saliency_args(sp_ctx *ctx, const void *logits, sp_dtype dtype, int64_t n_rows, int64_t vocab,
+                                     int64_t row_stride, const int32_t *target, const int32_t *row_path,
+                                     int32_t n_path_slots, sp_saliency_mode mode, const float *score) {
   if (!logits || !target || !row_path || !score) return fail(&ctx->err, SP_ERR_INVALID_ARG, "NULL argument");
   if (n_rows < 0 || vocab <= 0 || n_path_slots <= 0 || row_stride < vocab)
     return fail(&ctx->err, SP_ERR_INVALID_ARG, "bad sizes (n_rows >= 0, vocab > 0, n_path_slots > 0, row_stride >= vocab)");
@@ -580,11 +761,22 @@ extern "C" sp_status sp_path_saliency(sp_ctx *ctx, const void *logits, sp_dtype 
   const int64_t esz = dtype == SP_BF16 ? 2 : 4;
   if ((reinterpret_cast<uintptr_t>(logits) & 15) || (row_stride * esz) % 16)
     return fail(&ctx->err, SP_ERR_UNSUPPORTED, "logits base and row stride must be 16-byte aligned");
+  return SP_OK;
+}
+
+extern "C" sp_status sp_path_saliency(sp_ctx *ctx, const void *logits, sp_dtype dtype, int64_t n_rows,
+                                      int64_t vocab, int64_t row_stride, const int32_t *target,
+                                      const int32_t *row_path, const float *prior, int32_t n_path_slots,
+                                      sp_saliency_mode mode, float *score) {
+  if (!ctx) return fail(nullptr, SP_ERR_INVALID_ARG, "ctx is NULL");
+  sp_status st = check_saliency_args(ctx, logits, dtype, n_rows, vocab, row_stride, target, row_path, n_path_slots,
+                                     mode, score);
+  if (st != SP_OK) return st;
   SP_HIP(ctx, hipSetDevice(ctx->device));
-  sp_status st = ensure_ws(ctx, size_t(std::max<int64_t>(n_rows, 1)) * sizeof(float));
+  st = ensure_sal(ctx, n_path_slots);
   if (st != SP_OK) return st;
   hipError_t e = sp::launch_saliency(logits, dtype, n_rows, vocab, row_stride, target, row_path, prior,
-                                     n_path_slots, int(mode), ctx->ws, score, ctx->stream);
+                                     n_path_slots, int(mode), ctx->sal, score, ctx->stream);
   if (e != hipSuccess) return fail(&ctx->err, SP_ERR_HIP, "saliency launch: %s", hipGetErrorString(e));
   return SP_OK;
 }

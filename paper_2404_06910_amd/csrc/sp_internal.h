@@ -13,6 +13,14 @@ namespace sp {
 
 constexpr int kMaxRanges = 32;     // ancestor key ranges per row group (after merging neighbours)
 constexpr int kPrefillThreads = 256;
+constexpr int kMaxDevices = 64;
+// per-path accumulator of the saliency launch: fixed-point sum of log-likelihoods, scored rows, flags
+struct SalSlot {
+  unsigned long long sum;   // two's complement, 2^-36 units
+  uint32_t count;
+  uint32_t flags;           // 1: a row with lp = -inf, 2: +inf, 4: NaN
+};
+constexpr int kSalDefaultSlots = 16384;                             // path slots a new context has accumulators for
 
 // A run of segments fused on the query side: child segments that are packed directly behind
 // their parent continue the parent's causal sequence (Sec. 3.2: a chain is a classical prompt).
@@ -79,8 +87,21 @@ struct sp_ctx {
   int device = 0;
   hipStream_t stream = nullptr;
   std::string err;
-  float *ws = nullptr;        // workspace (per-row log-likelihoods)
-  size_t ws_bytes = 0;
+  int n_cu = 256;             // compute units of the device (read once)
+  // saliency accumulators (zero between launches); a block that became too small is kept until
+  // sp_destroy, because a captured graph may still name it
+  void *sal = nullptr;
+  int32_t sal_slots = 0;
+  std::vector<void *> retired;
+  // plan upload: one pinned staging buffer, one event that tells when its last copy has left it,
+  // and the device blocks of destroyed plans, kept for the next plan
+  void *stage = nullptr;
+  size_t stage_bytes = 0;
+  hipEvent_t stage_ev = nullptr;
+  bool stage_busy = false;
+  std::vector<std::pair<void *, size_t>> blob_pool;
+  int refs = 1;               // the context itself + every live plan made on it
+  bool closed = false;        // sp_destroy was called; the struct lives on until the last plan is gone
 };
 
 struct sp_plan {
@@ -108,8 +129,10 @@ struct sp_plan {
   std::vector<int32_t> path_off, shared_rng_beg, shared_rng_end, path_rng_beg, path_rng_end;
   std::vector<sp::KeyRange> dec_ranges;
   std::vector<int32_t> path_max_ranges;  // per prompt: max ranges of any single path
+  std::vector<float> pos, slopes;        // copies of tok_pos / alibi_slopes (empty when not given)
   // device copies (one allocation)
   void *dev_blob = nullptr;
+  size_t dev_blob_bytes = 0;  // capacity of the allocation
   sp::PlanDev dev{};
 };
 
@@ -127,7 +150,7 @@ hipError_t launch_prefill_f32(const sp_plan *plan, const PrefillArgs &a, hipStre
 
 hipError_t launch_saliency(const void *logits, sp_dtype dt, int64_t n_rows, int64_t vocab, int64_t row_stride,
                            const int32_t *target, const int32_t *row_path, const float *prior,
-                           int32_t n_slots, int mode, float *lp_ws, float *score, hipStream_t s);
+                           int32_t n_slots, int mode, void *scratch_dev, float *score, hipStream_t s);
 
 hipError_t launch_topk(const float *score, const int32_t *path_off, int32_t n_prompts, int32_t n_paths_max,
                        int32_t k, int32_t *kept, hipStream_t s);

@@ -19,14 +19,23 @@ __global__ __launch_bounds__(256) void topk_kernel(const float *__restrict__ sco
   const int b = blockIdx.x;
   const int base = path_off[b];
   int n = path_off[b + 1] - base;
-  n = n < 0 ? 0 : (n > n_cap ? n_cap : n);
-  for (int i = threadIdx.x; i < n; i += blockDim.x) s_sc[i] = score[base + i];
+  n = n < 0 ? 0 : n;
+  // a prompt with more paths than the caller's bound is still ranked completely: its scores are then
+  // read from global memory instead of the LDS copy (slower, never truncated)
+  const bool staged = n <= n_cap;
+  const float *sc = score + base;
+  if (staged)
+    for (int i = threadIdx.x; i < n; i += blockDim.x) s_sc[i] = sc[i];
   for (int j = n + threadIdx.x; j < k; j += blockDim.x) kept[(int64_t)b * k + j] = -1;
   __syncthreads();
   for (int i = threadIdx.x; i < n; i += blockDim.x) {
-    const float mine = s_sc[i];
+    const float mine = staged ? s_sc[i] : sc[i];
     int rank = 0;
-    for (int j = 0; j < n; ++j) rank += before(s_sc[j], j, mine, i) ? 1 : 0;
+    if (staged) {
+      for (int j = 0; j < n; ++j) rank += before(s_sc[j], j, mine, i) ? 1 : 0;
+    } else {
+      for (int j = 0; j < n; ++j) rank += before(sc[j], j, mine, i) ? 1 : 0;
+    }
     if (rank < k) kept[(int64_t)b * k + rank] = i;
   }
 }

@@ -139,11 +139,13 @@ def test_ignored_kept_entries_and_k_zero(ctx):
     _check(got[0], ref, "bf16", "k=0")
 
 
-def test_config5_full_size_sampled(ctx):
-    """64 prompts x 32 heads, 2 of 20 paths kept, 256 steps; the oracle checks sampled
-    (step, prompt) pairs, all heads."""
+@pytest.mark.parametrize("bias", [False, True], ids=["plain", "bias"])
+def test_config5_full_size_sampled(ctx, bias):
+    """64 prompts x 32 heads, 2 of 20 paths kept, 256 steps; the oracle checks 32 (step, prompt) pairs
+    spread over the steps (first, last, and a seeded sample in between), all heads; with bias = True the
+    cache carries equilibrium positions and every head a linear distance penalty."""
     wl = sp_synth.WORKLOADS["c5_decode_bf16"]
-    print("case: c5", flush=True)
+    print("case: c5 bias=%s" % bias, flush=True)
     rng = np.random.default_rng(wl.seed)
     st = sp_synth.forkjoin_segtable(wl.preamble_len, [[wl.doc_len] * wl.n_paths] * wl.n_prompts, wl.query_len)
     Bn, H, d, S = wl.n_prompts, wl.n_kv_heads, wl.head_dim, wl.decode_steps
@@ -155,24 +157,44 @@ def test_config5_full_size_sampled(ctx):
     dv = torch.randn((S, Bn, H, d), generator=g, device="cuda").to(torch.bfloat16)
     kept_np = np.stack([rng.permutation(wl.n_paths)[:wl.top_k] for _ in range(Bn)]).astype(np.int32)
     kept = dev(kept_np)
-    plan = make_plan(ctx, st, H, H, d, "bf16")
+    pos = slopes = pos_resp = None
+    new_pos = [None] * S
+    if bias:
+        a, dd, qq = orc.equilibrium_positions(wl.preamble_len, [wl.doc_len] * wl.n_paths, wl.query_len)
+        pos = np.zeros(st.n_tokens, np.float32)
+        for b in range(Bn):
+            s0 = st.seg_tok_start[st.preamble_seg[b]]; pos[s0:s0 + wl.preamble_len] = a
+            for i in range(wl.n_paths):
+                slot = st.path_off[b] + i
+                s0 = st.seg_tok_start[st.doc_seg[slot]]; pos[s0:s0 + wl.doc_len] = dd[i]
+                s0 = st.seg_tok_start[st.query_seg[slot]]; pos[s0:s0 + wl.query_len] = qq
+        slopes = sp_synth.geometric_slopes(H)
+        pos_resp = torch.zeros((Bn, S), device="cuda")
+        p0 = float(pos.max()) + 1.0
+        new_pos = [torch.full((Bn,), p0 + s, device="cuda") for s in range(S)]
+    plan = make_plan(ctx, st, H, H, d, "bf16", tok_pos=pos, slopes=slopes)
     Kr = torch.zeros((Bn, S, H, d), dtype=torch.bfloat16, device="cuda"); Vr = torch.zeros_like(Kr)
     outs = torch.empty((S, Bn, H, d), dtype=torch.bfloat16, device="cuda")
     for s in range(S):
         ctx.sp_pruned_decode(plan, kept, wl.top_k, K, V, Kr, Vr, S, dq[s], dk[s], dv[s], outs[s], 1 / math.sqrt(d),
-                             resp_len_add=s)
+                             resp_len_add=s, pos_resp=pos_resp, new_pos=new_pos[s])
     torch.cuda.synchronize()
     assert torch.equal(Kr, dk.transpose(0, 1)) and torch.equal(Vr, dv.transpose(0, 1))
     assert not torch.isnan(outs.float()).any()
-    for s, b in [(0, 0), (1, 63), (37, 5), (128, 31), (255, 17), (255, 63)]:
+    pairs = [(0, 0), (1, 63), (255, 17), (255, 63)] + [(int(rng.integers(0, S)), int(rng.integers(0, Bn))) for _ in range(28)]
+    for s, b in pairs:
         idx = orc.joined_cache_index(st.prompt_seg_off, st.seg_tok_start, st.seg_tok_len, st.seg_path, b, kept_np[b])
         assert len(idx) == 64 + 2 * 152
         tok = torch.from_numpy(idx).cuda()
         kp = np.zeros((st.n_tokens, H, d), np.float32); vp = np.zeros_like(kp)     # only gathered rows are filled
         kp[idx] = K[tok].float().cpu().numpy(); vp[idx] = V[tok].float().cpu().numpy()
+        kw = {}
+        if bias:
+            kw = dict(pos_prefill=pos, pos_resp=np.array([p0 + i for i in range(s)], np.float64), pos_new=p0 + s,
+                      alibi_slopes=slopes)
         ref = orc.pruned_decode_step(dq[s, b].float().cpu().numpy(), dk[s, b].float().cpu().numpy(),
                                      dv[s, b].float().cpu().numpy(), kp, vp, idx, dk[:s, b].float().cpu().numpy(),
-                                     dv[:s, b].float().cpu().numpy(), 1 / math.sqrt(d))
+                                     dv[:s, b].float().cpu().numpy(), 1 / math.sqrt(d), **kw)
         _check(outs[s, b].float().cpu().numpy(), ref, "bf16", "c5 step %d prompt %d" % (s, b))
 
 

@@ -10,6 +10,7 @@ import sp_synth
 from oracle import sp_oracle as orc
 from paper_2404_06910_amd import binding as B
 
+from fullsize_oracle import oracle_by_segment as _oracle_by_segment
 from gpu_util import check_attn, covered_tokens, dev, make_plan, run_prefill
 
 pytestmark = pytest.mark.gpu
@@ -292,23 +293,36 @@ def test_head_major_kv_cache_layout(ctx, dtype, Hq, Hkv):
 FULL = ["c2_mha7b_bf16", "c3_ragged_bf16", "c4_gqa_bf16"]
 
 
+def _check_every_pair(got, st, q, k, v, scale, name, tok_pos=None, slopes=None):
+    """Every (prompt, head) pair, every row, element by element."""
+    Hq = q.shape[1]
+    worst = 0.0
+    for b in range(st.n_prompts):
+        toks, ref = _oracle_by_segment(st, q, k, v, scale, b, list(range(Hq)), tok_pos, slopes)
+        for h in range(Hq):
+            mx, _ = check_attn(got[toks, h], ref[:, h], "bf16", "%s b%d h%d" % (name, b, h))
+            worst = max(worst, mx)
+        print("  %s prompt %d: all %d heads ok (max-abs so far %.4f)" % (name, b, Hq, worst), flush=True)
+
+
 @pytest.mark.parametrize("name", FULL)
-def test_full_size_sampled_prompt_head_pairs(ctx, name):
-    """Full workload shape in the launch configuration the benchmark times; the oracle
-    evaluates sampled (prompt, head) pairs completely (all tokens of the prompt)."""
+def test_full_size_every_prompt_head_pair(ctx, name):
+    """Full workload shape in the launch configuration the benchmark times: EVERY (prompt, head) pair and
+    every token row against the oracle, element by element; two pairs are also evaluated by the oracle's
+    dense whole-prompt call."""
     wl = sp_synth.WORKLOADS[name]
     print("case:", name, flush=True)
     inp = sp_synth.make_inputs(wl, with_logits=False, with_decode=False)
     st = inp.st
     got, plan = run_prefill(ctx, st, inp.q, inp.k, inp.v, "bf16")
     assert not np.isnan(got[covered_tokens(st)]).any()
-    rng = np.random.default_rng(1)
-    n_samples = 3 if name == "c3_ragged_bf16" else 5
     scale = 1 / math.sqrt(wl.head_dim)
-    for _ in range(n_samples):
+    _check_every_pair(got, st, inp.q, inp.k, inp.v, scale, name)
+    rng = np.random.default_rng(1)
+    for _ in range(1 if name == "c3_ragged_bf16" else 2):
         b = int(rng.integers(0, wl.n_prompts)); h = int(rng.integers(0, wl.n_q_heads))
         ref = _oracle(st, inp.q, inp.k, inp.v, scale, prompts=[b], heads=[h])
-        check_attn(got, ref, "bf16", "%s b%d h%d" % (name, b, h))
+        check_attn(got, ref, "bf16", "%s dense b%d h%d" % (name, b, h))
     # property at full size: constant V rows give that constant back whatever the mask (softmax sums to 1)
     V1 = torch.ones(inp.v.shape, dtype=torch.bfloat16, device="cuda") * 0.5
     Q, K = dev(inp.q, "bf16"), dev(inp.k, "bf16")
@@ -316,3 +330,25 @@ def test_full_size_sampled_prompt_head_pairs(ctx, name):
     ctx.sp_forkjoin_prefill(plan, Q, K, V1, O, scale)
     torch.cuda.synchronize()
     assert torch.all((O.float() - 0.5).abs() <= 2 ** -8)
+
+
+def test_full_size_ragged_with_equilibrium_bias_every_pair(ctx):
+    """The ragged workload with equilibrium positions (Sec. 3.2.2 Eq. 1, from the oracle) and a linear
+    distance penalty per head: the BIAS kernel variant at the size the benchmark times, every pair."""
+    wl = sp_synth.WORKLOADS["c3_ragged_bf16"]
+    print("case: c3 + bias", flush=True)
+    inp = sp_synth.make_inputs(wl, with_logits=False, with_decode=False)
+    st = inp.st
+    pos = np.zeros(st.n_tokens, np.float32)
+    for b in range(st.n_prompts):
+        slots = range(int(st.path_off[b]), int(st.path_off[b + 1]))
+        lens = [int(st.seg_tok_len[st.doc_seg[s]]) for s in slots]
+        a, dd, qq = orc.equilibrium_positions(wl.preamble_len, lens, wl.query_len)
+        s0 = st.seg_tok_start[st.preamble_seg[b]]; pos[s0:s0 + wl.preamble_len] = a
+        for i, s in enumerate(slots):
+            s0 = st.seg_tok_start[st.doc_seg[s]]; pos[s0:s0 + lens[i]] = dd[i]
+            s0 = st.seg_tok_start[st.query_seg[s]]; pos[s0:s0 + wl.query_len] = qq
+    slopes = sp_synth.geometric_slopes(wl.n_q_heads)
+    got, _ = run_prefill(ctx, st, inp.q, inp.k, inp.v, "bf16", tok_pos=pos, slopes=slopes)
+    _check_every_pair(got, st, inp.q, inp.k, inp.v, 1 / math.sqrt(wl.head_dim), "c3+bias", pos.astype(np.float64),
+                      slopes)

@@ -84,8 +84,10 @@ def test_saliency_closed_forms(ctx):
 
 
 @pytest.mark.parametrize("name", ["c2_mha7b_bf16", "c3_ragged_bf16", "c4_gqa_bf16"])
-def test_full_size_saliency_sampled_slots(ctx, name):
-    """Full logit matrix generated on the device (seeded); the oracle scores sampled path slots."""
+def test_full_size_saliency_every_slot(ctx, name):
+    """Full logit matrix generated on the device (seeded); the oracle scores EVERY path slot (rows are
+    copied back a few hundred at a time).  Two launches on the same input give bit-identical scores
+    (integer accumulation: no dependence on the order in which rows finish)."""
     wl = sp_synth.WORKLOADS[name]
     print("case:", name, flush=True)
     n_slots = wl.n_prompts * wl.n_paths
@@ -101,16 +103,57 @@ def test_full_size_saliency_sampled_slots(ctx, name):
     row_path = np.repeat(np.arange(n_slots), wl.query_len).astype(np.int32)
     got = _saliency(ctx, logits, target, row_path, n_slots)
     assert np.isfinite(got).all()
-    for slot in rng.choice(n_slots, size=12, replace=False):
-        rows = slice(slot * wl.query_len, (slot + 1) * wl.query_len)
+    again = _saliency(ctx, logits, target, row_path, n_slots)
+    assert np.array_equal(got, again)
+    per = 16                                                # slots per copy
+    for s0 in range(0, n_slots, per):
+        s1 = min(n_slots, s0 + per)
+        rows = slice(s0 * wl.query_len, s1 * wl.query_len)
         x = logits[rows].float().cpu().numpy()
-        ref = orc.path_saliency(x, target[rows], np.zeros(wl.query_len, np.int64), 1)[0]
-        np.testing.assert_allclose(got[slot], ref, rtol=REL)
+        ref = orc.path_saliency(x, target[rows], row_path[rows] - s0, s1 - s0)
+        np.testing.assert_allclose(got[s0:s1], ref, rtol=REL)
     # chained top-k on the device scores equals the oracle's top-k of the same scores
     off = np.arange(0, n_slots + 1, wl.n_paths).astype(np.int32)
     kept = torch.empty((wl.n_prompts, wl.top_k), dtype=torch.int32, device="cuda")
     ctx.sp_prune_topk(dev(got), dev(off), wl.n_prompts, wl.n_paths, wl.top_k, kept)
     assert np.array_equal(kept.cpu().numpy(), orc.prune_topk(got, off, wl.top_k))
+
+
+def test_saliency_scattered_rows_many_slots_and_nonfinite(ctx):
+    """Rows of a path scattered over the matrix (the fused reduction does not assume runs), more slots
+    than rows, a slot whose rows hold -inf and NaN log-likelihoods, MEAN counts, repeatability."""
+    rng = np.random.default_rng(21)
+    R, n, vocab = 700, 900, 2048
+    x = sp_synth.round_to_dtype(rng.standard_normal((R, vocab), dtype=np.float32) * 3, "f32")
+    tgt = rng.integers(0, vocab, size=R).astype(np.int32)
+    rp = rng.integers(0, n, size=R).astype(np.int32)
+    rp[:40] = 7                                             # one crowded slot
+    x[3, tgt[3]] = -np.inf                                  # lp = -inf in slot 7
+    x[50, :] = np.nan; rp[50] = 11                          # lp = NaN in slot 11
+    tgt[[5, 6]] = -1
+    X = dev(x, "f32")
+    for mode, name in ((B.SALIENCY_SUM, "sum"), (B.SALIENCY_MEAN, "mean")):
+        got = _saliency(ctx, X, tgt, rp, n, mode=mode)
+        with np.errstate(invalid="ignore", divide="ignore"):
+            ref = orc.path_saliency(x, tgt, rp, n, mode=name)
+        assert np.isneginf(got[7]) and np.isneginf(ref[7]) and np.isnan(got[11]) and np.isnan(ref[11])
+        ok = np.isfinite(ref)
+        np.testing.assert_allclose(got[ok], ref[ok], rtol=REL, atol=1e-5)
+        assert np.array_equal(got, _saliency(ctx, X, tgt, rp, n, mode=mode), equal_nan=True)
+
+
+def test_saliency_more_slots_than_the_initial_workspace(ctx):
+    """A call with more path slots than a new context has accumulators for grows them once; results
+    before and after the growth agree with the oracle."""
+    rng = np.random.default_rng(4)
+    R, n, vocab = 64, 20000, 512
+    x = sp_synth.round_to_dtype(rng.standard_normal((R, vocab), dtype=np.float32), "bf16")
+    tgt = rng.integers(0, vocab, size=R).astype(np.int32)
+    rp = rng.integers(0, n, size=R).astype(np.int32)
+    got = _saliency(ctx, dev(x, "bf16"), tgt, rp, n)
+    _close(got, orc.path_saliency(x, tgt, rp, n))
+    got = _saliency(ctx, dev(x, "bf16"), tgt, rp % 100, 100)
+    _close(got, orc.path_saliency(x, tgt, rp % 100, 100))
 
 
 # ----------------------------------------------------------------------------- top-k
@@ -137,6 +180,15 @@ def test_topk_random_ragged_prompts(ctx):
             ref = orc.prune_topk(sc[off[b]:off[b + 1]], [0, n], kk)[0]
             assert got[b, :kk].tolist() == ref.tolist()
             assert np.all(got[b, kk:] == -1)
+
+
+def test_topk_prompt_larger_than_the_stated_bound_is_not_truncated(ctx):
+    rng = np.random.default_rng(8)
+    sizes = [300, 5, 64]
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    sc = rng.standard_normal(off[-1]).astype(np.float32)
+    got = _topk(ctx, sc, off, 4, n_max=64)                  # the first prompt has 300 paths
+    assert np.array_equal(got, orc.prune_topk(sc, off, 4))
 
 
 def test_topk_ties_zero_signs_inf_nan_full_ranking(ctx):

@@ -231,3 +231,82 @@ def test_kv_bytes_per_token_golden():
     layers, hidden, esz, expect, quote = (int(x) for x in row)
     got = layers * bench.kv_bytes_per_token(n_kv_heads=32, head_dim=hidden // 32, elem_bytes=esz)
     assert got == expect and round(got / 1000) == quote
+
+
+def _check_work_list(t, Hq, Hkv, cached=None):
+    """The permuted work list covers every computed (token row, query head) exactly once, its key counts
+    equal the oracle mask's row sums, and every worker slot owns one contiguous slice."""
+    p = _plan(t, Hq=Hq, Hkv=Hkv, d=128, seg_cached=cached)
+    items, begin = p.work_items()
+    rng_tab = p.key_ranges()
+    assert begin[0] == 0 and begin[-1] == len(items) and np.all(np.diff(begin) >= 0)
+    G = Hq // Hkv
+    hpw = 4 if G % 4 == 0 else 2 if G % 2 == 0 else 1
+    seen = np.zeros((t["n_tokens"], Hq), np.int32)
+    vis = np.zeros(t["n_tokens"], np.int64)                 # visible keys per token, from the oracle's explicit mask
+    for b in range(len(t["prompt_seg_off"]) - 1):
+        ids = np.arange(t["prompt_seg_off"][b], t["prompt_seg_off"][b + 1])
+        toks, M = orc.dag_mask(t["seg_tok_start"], t["seg_tok_len"], t["seg_parent"], ids)
+        vis[toks] = M.sum(axis=1)
+    for tok_start, row0, n_rows, anc, r_off, n_rng, heads, r0_start in items:
+        h0, kv = heads & 0xffff, heads >> 16
+        assert kv == h0 // G and n_rows >= 1 and h0 % hpw == 0
+        assert sum(int(rng_tab[r_off + r][1]) for r in range(n_rng)) == anc
+        if n_rng:
+            assert rng_tab[r_off][0] == r0_start
+        for r in range(n_rows):
+            tok = tok_start + row0 + r
+            assert vis[tok] == anc + row0 + r + 1           # ancestors completely, own run causally
+            seen[tok, h0:h0 + hpw] += 1
+    live = np.zeros(t["n_tokens"], bool)
+    for s in range(len(t["seg_tok_len"])):
+        if cached is None or not cached[s]:
+            live[t["seg_tok_start"][s]:t["seg_tok_start"][s] + t["seg_tok_len"][s]] = True
+    assert np.all(seen[live] == 1) and np.all(seen[~live] == 0)
+    p.close()
+
+
+def test_work_list_covers_every_row_and_head_once():
+    rng = np.random.default_rng(11)
+    for trial in range(6):
+        t = _random_table(rng, int(rng.integers(1, 4)))
+        for Hq, Hkv in ((4, 4), (4, 2), (8, 2)):
+            _check_work_list(t, Hq, Hkv)
+        cached = (rng.random(len(t["seg_tok_len"])) < 0.4).astype(np.uint8)
+        _check_work_list(t, 4, 1, cached=cached)
+    for name in ("c2_mha7b_bf16", "c4_gqa_bf16"):
+        wl = sp_synth.WORKLOADS[name]
+        st = sp_synth.forkjoin_segtable(wl.preamble_len, [[wl.doc_len] * wl.n_paths] * 2, wl.query_len)
+        t = dict(prompt_seg_off=st.prompt_seg_off, seg_tok_start=st.seg_tok_start, seg_tok_len=st.seg_tok_len,
+                 seg_parent=st.seg_parent, seg_path=st.seg_path, n_tokens=st.n_tokens)
+        _check_work_list(t, wl.n_q_heads, wl.n_kv_heads)
+
+
+def test_work_list_is_balanced_over_the_worker_slots():
+    """Load per worker slot (key stages + per-item overhead) stays within a few items of the mean."""
+    wl = sp_synth.WORKLOADS["c2_mha7b_bf16"]
+    st = sp_synth.forkjoin_segtable(wl.preamble_len, [[wl.doc_len] * wl.n_paths] * wl.n_prompts, wl.query_len)
+    p = B.Plan(None, st.prompt_seg_off, st.seg_tok_start, st.seg_tok_len, st.seg_parent, st.seg_path, st.n_tokens,
+               wl.n_q_heads, wl.n_kv_heads, wl.head_dim, B.SP_BF16)
+    items, begin = p.work_items()
+    cost = 2 + (items[:, 3] + items[:, 1] + items[:, 2] + 31) // 32
+    load = np.add.reduceat(cost, begin[:-1])[np.diff(begin) > 0]
+    assert len(load) == len(begin) - 1                      # every slot has work at this size
+    assert load.max() <= 1.25 * load.mean() and load.min() >= 0.75 * load.mean()
+    p.close()
+
+
+def test_plan_update_rebuilds_in_place_and_keeps_the_plan_on_error():
+    rng = np.random.default_rng(3)
+    t1, t2 = _random_table(rng, 2), _random_table(rng, 3)
+    p = _plan(t1)
+    ref2 = _plan(t2)
+    p.update(t2["prompt_seg_off"], t2["seg_tok_start"], t2["seg_tok_len"], t2["seg_parent"], t2["seg_path"], t2["n_tokens"])
+    assert p.info() == ref2.info() and p.visible_pairs() == ref2.visible_pairs()
+    a, b = p.work_items(), ref2.work_items()
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    bad = dict(t1); bad["seg_parent"] = t1["seg_parent"].copy(); bad["seg_parent"][1] = 1
+    with pytest.raises(B.SpError) as e:
+        p.update(bad["prompt_seg_off"], bad["seg_tok_start"], bad["seg_tok_len"], bad["seg_parent"], bad["seg_path"], bad["n_tokens"])
+    assert e.value.status == -2
+    assert p.info() == ref2.info()                          # unchanged after the failed update

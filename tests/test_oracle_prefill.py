@@ -256,3 +256,23 @@ def test_deeper_chain_matches_causal_attention():
     q, k, v = _rand_qkv(rng, T, 1, 1, 8)
     out = orc.forkjoin_prefill(q, k, v, np.array([0, 4]), start, np.array(lens, np.int32), parent, 0.35)
     np.testing.assert_allclose(out[:, 0], _sdpa_causal(q[:, 0], k[:, 0], v[:, 0], 0.35), rtol=1e-11, atol=1e-13)
+
+
+from fullsize_oracle import oracle_by_segment  # noqa: E402
+
+
+def test_segment_wise_oracle_equals_dense_oracle():
+    """The restricted evaluation used at full size gives what the oracle's dense
+    per-prompt evaluation gives, to fp64 rounding, with and without the distance bias."""
+    rng = np.random.default_rng(9)
+    st = sp_synth.forkjoin_segtable(19, [[40, 7, 33], [12, 50]], 6, "grouped")
+    f = lambda *s: sp_synth.round_to_dtype(rng.standard_normal(s, dtype=np.float32), "bf16")
+    q, k, v = f(st.n_tokens, 4, 64), f(st.n_tokens, 2, 64), f(st.n_tokens, 2, 64)
+    pos = sp_synth.classical_positions(st) * 0.75
+    slopes = sp_synth.geometric_slopes(4)
+    for kw in ({}, {"tok_pos": pos, "alibi_slopes": slopes}):
+        dense = orc.forkjoin_prefill(q, k, v, st.prompt_seg_off, st.seg_tok_start, st.seg_tok_len, st.seg_parent, 0.125, **kw)
+        for b in range(2):
+            toks, out = oracle_by_segment(st, q, k, v, 0.125, b, [0, 3], kw.get("tok_pos"), kw.get("alibi_slopes"))
+            np.testing.assert_allclose(out[:, 0], dense[toks, 0], rtol=0, atol=1e-12)
+            np.testing.assert_allclose(out[:, 1], dense[toks, 3], rtol=0, atol=1e-12)
