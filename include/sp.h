@@ -176,6 +176,19 @@ sp_status sp_forkjoin_prefill(sp_ctx *ctx, const sp_plan *plan, const void *Q, c
 sp_status sp_path_saliency(sp_ctx *ctx, const void *logits, sp_dtype dtype, int64_t n_rows, int64_t vocab,
                            int64_t row_stride, const int32_t *target, const int32_t *row_path,
                            const float *prior, int32_t n_path_slots, sp_saliency_mode mode, float *score);
+/*
+ * sp_path_saliency for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments, same result, but the
+ * per-path accumulators live in a static device array of the library (16384 path slots, 256 KiB + 256 B
+ * per GPU, held until the process ends) instead of the context's workspace, and the call makes no
+ * hipMalloc / hipFree.  n_path_slots above 16384 returns SP_ERR_UNSUPPORTED.  The array is shared by every
+ * call on that GPU: calls that overlap in time on one GPU (different streams or contexts) race; calls on
+ * one stream are safe.  Each launch leaves the accumulators it used at zero, the state the next one expects.
+ */
+sp_status sp_path_saliency_static(sp_ctx *ctx, const void *logits, sp_dtype dtype, int64_t n_rows, int64_t vocab,
+                                  int64_t row_stride, const int32_t *target, const int32_t *row_path,
+                                  const float *prior, int32_t n_path_slots, sp_saliency_mode mode, float *score);
+
 /* ---- a3: top-k pruning (Sec. 3.2.3; Alg. 3) -------------------------------------------- */
 /*
  * Per prompt b, the k local path indices with the largest score, in descending score order,

@@ -67,6 +67,7 @@ def lib() -> C.CDLL:
         "sp_plan_joined_keys": (i64, [vp, i32, vp, i32, vp, i64]),
         "sp_forkjoin_prefill": (C.c_int, [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, f32]),
         "sp_path_saliency": (C.c_int, [vp, vp, C.c_int, i64, i64, i64, vp, vp, vp, i32, C.c_int, vp]),
+        "sp_path_saliency_static": (C.c_int, [vp, vp, C.c_int, i64, i64, i64, vp, vp, vp, i32, C.c_int, vp]),
         "sp_prune_topk": (C.c_int, [vp, vp, vp, i32, i32, i32, vp]),
         "sp_pruned_decode": (C.c_int, [vp, vp, vp, i32, vp, vp, i64, i64, vp, vp, vp, i32, vp, i32, vp, vp, vp, vp,
                                        vp, f32]),
@@ -172,6 +173,11 @@ class Context:
                                            _dev(row_path, "row_path"), _dev(prior, "prior"), int(n_path_slots),
                                            int(mode), _dev(score, "score")))
         return score
+
+    def sp_path_saliency_static(self, logits, target, row_path, n_path_slots: int, score, prior=None,
+                                mode: int = SALIENCY_SUM):
+        return self.sp_path_saliency(logits, target, row_path, n_path_slots, score, prior, mode,
+                                     _entry="sp_path_saliency_static")
 
     # -- a3 ------------------------------------------------------------------------------
     def sp_prune_topk(self, score, path_off, n_prompts: int, n_paths_max: int, k: int, kept):

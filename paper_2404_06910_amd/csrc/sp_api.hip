@@ -781,6 +781,29 @@ extern "C" sp_status sp_path_saliency(sp_ctx *ctx, const void *logits, sp_dtype 
   return SP_OK;
 }
 
+// The same computation for callers that cannot allocate: the accumulators are the library's static
+// device array (one copy per GPU, shared by every call on that GPU).
+extern "C" sp_status sp_path_saliency_static(sp_ctx *ctx, const void *logits, sp_dtype dtype, int64_t n_rows,
+                                             int64_t vocab, int64_t row_stride, const int32_t *target,
+                                             const int32_t *row_path, const float *prior, int32_t n_path_slots,
+                                             sp_saliency_mode mode, float *score) {
+  if (!ctx) return fail(nullptr, SP_ERR_INVALID_ARG, "ctx is NULL");
+  sp_status st = check_saliency_args(ctx, logits, dtype, n_rows, vocab, row_stride, target, row_path, n_path_slots,
+                                     mode, score);
+  if (st != SP_OK) return st;
+  if (n_path_slots > sp::kSalStaticSlots)
+    return fail(&ctx->err, SP_ERR_UNSUPPORTED, "n_path_slots %d exceeds the static scratch (%d slots)", n_path_slots,
+                sp::kSalStaticSlots);
+  SP_HIP(ctx, hipSetDevice(ctx->device));
+  void *scratch_dev = nullptr;
+  hipError_t e = sp::saliency_static_scratch(ctx->device, &scratch_dev);
+  if (e != hipSuccess) return fail(&ctx->err, SP_ERR_HIP, "static scratch address: %s", hipGetErrorString(e));
+  e = sp::launch_saliency(logits, dtype, n_rows, vocab, row_stride, target, row_path, prior, n_path_slots, int(mode),
+                          scratch_dev, score, ctx->stream);
+  if (e != hipSuccess) return fail(&ctx->err, SP_ERR_HIP, "saliency launch: %s", hipGetErrorString(e));
+  return SP_OK;
+}
+
 // ---------------------------------------------------------------------------------------
 // a3 top-k
 // ---------------------------------------------------------------------------------------

@@ -21,6 +21,8 @@ struct SalSlot {
   uint32_t flags;           // 1: a row with lp = -inf, 2: +inf, 4: NaN
 };
 constexpr int kSalDefaultSlots = 16384;                             // path slots a new context has accumulators for
+constexpr int kSalStaticSlots = 16384;                              // path slots of the no-allocation entry point
+constexpr size_t kSalStaticBytes = 256 + sizeof(SalSlot) * size_t(kSalStaticSlots);
 
 // A run of segments fused on the query side: child segments that are packed directly behind
 // their parent continue the parent's causal sequence (Sec. 3.2: a chain is a classical prompt).
@@ -151,6 +153,7 @@ hipError_t launch_prefill_f32(const sp_plan *plan, const PrefillArgs &a, hipStre
 hipError_t launch_saliency(const void *logits, sp_dtype dt, int64_t n_rows, int64_t vocab, int64_t row_stride,
                            const int32_t *target, const int32_t *row_path, const float *prior,
                            int32_t n_slots, int mode, void *scratch_dev, float *score, hipStream_t s);
+hipError_t saliency_static_scratch(int device, void **out);
 
 hipError_t launch_topk(const float *score, const int32_t *path_off, int32_t n_prompts, int32_t n_paths_max,
                        int32_t k, int32_t *kept, hipStream_t s);

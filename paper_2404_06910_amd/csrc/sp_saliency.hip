@@ -8,6 +8,8 @@
 // set a flag bit of the slot instead.  A launch-wide counter finds the workgroup that finishes last; it
 // turns the sums into scores (SUM or MEAN, plus the prior) and puts every accumulator it used back to
 // zero, which is the state the next launch expects.
+#include <mutex>
+
 #include "sp_device.h"
 #include "sp_internal.h"
 
@@ -17,6 +19,10 @@ constexpr int kSalThreads = 256;
 constexpr int kSalUnroll = 4;      // 16-byte vectors in flight per thread and step
 constexpr double kFixOne = 68719476736.0;        // 2^36
 constexpr float kFixLimit = 6.0e7f;              // |lp| above this (about 2^26) is treated as infinite
+
+// Scratch of the entry point that allocates nothing: the launch counter plus one SalSlot per path slot,
+// kSalStaticBytes on every GPU the library runs on, zero at load and left at zero by every launch.
+static __device__ __align__(256) unsigned char scratch[kSalStaticBytes];
 
 template <typename T>
 __global__ __launch_bounds__(kSalThreads) void saliency_kernel(const T *__restrict__ logits, int64_t vocab,
@@ -168,6 +174,24 @@ hipError_t launch_saliency(const void *logits, sp_dtype dt, int64_t n_rows, int6
                        static_cast<const float *>(logits), vocab, row_stride, target, row_path, prior, n_slots, mode,
                        acc, done, score);
   return hipGetLastError();
+}
+
+// Address of this device's copy of the static scratch array.  In host code the array's name is only a
+// stand-in, not a device address: the address comes from the runtime, once per device, with that device
+// current (the caller has made it current), and is kept per device.
+hipError_t saliency_static_scratch(int device, void **out) {
+  static std::mutex mu;
+  static void *ptrs[kMaxDevices] = {};
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptrs[device]) {
+    void *p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    ptrs[device] = p;
+  }
+  *out = ptrs[device];
+  return hipSuccess;
 }
 
 }  // namespace sp
