@@ -22,6 +22,9 @@ What each function follows (all citations are to the superposition-prompting pap
                                 they are) and Alg. 3: cache = preamble + kept (doc+query)
                                 pairs + response so far; one new token per step.
   equilibrium_positions         Sec. 3.2.2 Eq. 1, App. B.2 Eq. 3 and Alg. 1.
+  equilibrium_positions_tree    the same rule read for any prompt tree (iterative
+                                superposition, Sec. 4.1.2, puts forks behind chains of kept
+                                documents): Eq. 1 applied to the children of every node.
 
 Pins (tests/test_oracle_*.py): per-path equivalence with textbook causal attention,
 single-document reduction to a library causal-attention routine, independence of paths,
@@ -281,3 +284,41 @@ def equilibrium_positions(preamble_len, doc_lens, query_len):
     pos_d = [arange_positions(first, S / float(L), L) for L in doc_lens]
     pos_q = arange_positions(first + S, 1.0, query_len)
     return pos_p, pos_d, pos_q
+
+
+def equilibrium_positions_tree(seg_parent, seg_tok_len):
+    """Equilibrium positions for a forest of segments (a reading of Sec. 3.2.2 Eq. 1 and App. B.2
+    Alg. 1 for prompt trees that are not a single ForkJoin, e.g. the rounds of iterative
+    superposition in Sec. 4.1.2).
+
+    Alg. 1 places the documents that fork behind the preamble: they start right after the
+    preamble's last position and document i advances by S/|d_i| per token, S the harmonic mean of
+    the sibling lengths (Eq. 1), so all siblings cover the same span S.  Read per node of the tree:
+    a root segment sits at 0, 1, 2, ...; the children c_1..c_n of a node start where the node's own
+    span ends and child i advances by S/|c_i| per token with S = n / sum_i 1/|c_i|; a child's span
+    ends S after its start.  A single child has S = |c|, i.e. it simply continues with step 1 --
+    which is the query rule of Alg. 3 (the query copy follows its document one span after the
+    preamble) and the classical spacing of a chain of kept documents.
+
+    seg_parent[s] is the parent segment of s or -1; parents come before their children.
+    Returns a list with one fp64 position array per segment.
+    """
+    n = len(seg_parent)
+    children = [[] for _ in range(n)]
+    for s in range(n):
+        if int(seg_parent[s]) >= 0:
+            children[int(seg_parent[s])].append(s)
+    pos = [None] * n
+    end = [0.0] * n                                   # where the segment's span ends
+    for s in range(n):
+        par = int(seg_parent[s])
+        L = int(seg_tok_len[s])
+        if par < 0:
+            pos[s] = arange_positions(0.0, 1.0, L)
+            end[s] = float(L)
+        else:
+            S = harmonic_span([int(seg_tok_len[c]) for c in children[par]])
+            pos[s] = arange_positions(end[par], S / float(L), L)
+            end[s] = end[par] + S
+    return pos
+

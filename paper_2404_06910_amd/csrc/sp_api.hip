@@ -863,6 +863,15 @@ extern "C" sp_status sp_pruned_decode(sp_ctx *ctx, const sp_plan *plan, const in
 // ---------------------------------------------------------------------------------------
 // Equilibrium positions (Sec. 3.2.2 Eq. 1; App. B.2 Eq. 3 and Alg. 1; query rule of Alg. 3)
 // ---------------------------------------------------------------------------------------
+// Alg. 1 spaces the documents that fork behind the preamble by S/|d_i| (S the harmonic mean of their
+// lengths, Eq. 1), so that all of them span [P, P + S).  Alg. 3 writes the query's start as the last
+// position of document 1 with no "+ 1" and for document 1 only; it is read here as "one document span
+// after the preamble", P + S, shared by all query copies with step 1: the only reading under which
+// equal-length documents give exactly the classical positions of [preamble; document; query], which
+// Sec. 3.2 requires of the ForkJoin prompt.  The same rule is applied to the children of EVERY node, so
+// that iterated superposition (Sec. 4.1.2: forks behind a chain of kept documents) is covered: the
+// children of a node start where the node's span ends, advance by S/len with S the harmonic mean of the
+// sibling lengths, and an only child therefore continues with step 1.
 extern "C" sp_status sp_equilibrium_positions(const sp_segtable *t, float *out) {
   if (!out) return fail(nullptr, SP_ERR_INVALID_ARG, "tok_pos_out is NULL");
   sp_segtable tt;

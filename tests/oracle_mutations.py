@@ -40,4 +40,10 @@ MUTATIONS = [
      "    pos_d = [arange_positions(first, 1.0, L) for L in doc_lens]"),
     ("queries start one position early", "    pos_q = arange_positions(first + S, 1.0, query_len)",
      "    pos_q = arange_positions(first + S - 1.0, 1.0, query_len)"),
+    ("tree: a child's span ends after its token count instead of the sibling span", "            end[s] = end[par] + S",
+     "            end[s] = end[par] + float(L)"),
+    ("tree: children start at the parent's last position", "            pos[s] = arange_positions(end[par], S / float(L), L)",
+     "            pos[s] = arange_positions(end[par] - 1.0, S / float(L), L)"),
+    ("tree: sibling span taken over all segments with any parent", "            S = harmonic_span([int(seg_tok_len[c]) for c in children[par]])",
+     "            S = harmonic_span([int(seg_tok_len[c]) for c in range(n) if int(seg_parent[c]) >= 0])"),
 ]

@@ -310,3 +310,19 @@ def test_plan_update_rebuilds_in_place_and_keeps_the_plan_on_error():
         p.update(bad["prompt_seg_off"], bad["seg_tok_start"], bad["seg_tok_len"], bad["seg_parent"], bad["seg_path"], bad["n_tokens"])
     assert e.value.status == -2
     assert p.info() == ref2.info()                          # unchanged after the failed update
+
+
+def test_equilibrium_helper_equals_the_tree_oracle_on_random_forests():
+    """sp_equilibrium_positions applies Eq. 1 to the children of every node; the oracle's tree function
+    (pinned by hand-worked fractions) is its reference on forests that are not ForkJoin-shaped: chains of
+    shared segments, forks behind chains, several subtrees per path."""
+    rng = np.random.default_rng(17)
+    for _ in range(25):
+        t = _random_table(rng, int(rng.integers(1, 4)))
+        got = B.equilibrium_positions(t["prompt_seg_off"], t["seg_tok_start"], t["seg_tok_len"], t["seg_parent"],
+                                      t["seg_path"], t["n_tokens"])
+        ref = orc.equilibrium_positions_tree(t["seg_parent"], t["seg_tok_len"])
+        for s in range(len(ref)):
+            a = int(t["seg_tok_start"][s])
+            np.testing.assert_allclose(got[a:a + len(ref[s])], ref[s], rtol=1e-6, atol=1e-6)
+

@@ -116,3 +116,54 @@ def test_equilibrium_positions_properties():
         lens = rng.integers(1, 300, size=rng.integers(1, 30))
         S = orc.harmonic_span(lens)
         assert lens.min() - 1e-9 <= S <= lens.mean() + 1e-9
+
+
+def test_tree_positions_match_hand_worked_fractions():
+    from fractions import Fraction
+    path = os.path.join(os.path.dirname(__file__), "golden", "tree_positions.txt")
+    n = 0
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        parents, lens, expect = [x.strip() for x in line.split(";")]
+        parents = [int(x) for x in parents.split(",")]
+        lens = [int(x) for x in lens.split(",")]
+        got = orc.equilibrium_positions_tree(parents, lens)
+        want = [[float(Fraction(x)) for x in seg.split()] for seg in expect.split("|")]
+        assert len(got) == len(want)
+        for g, w in zip(got, want):
+            np.testing.assert_allclose(g, w, rtol=0, atol=1e-12)
+        n += 1
+    assert n == 3
+
+
+def test_tree_positions_reduce_to_alg1_on_forkjoin_and_obey_the_span_rule():
+    rng = np.random.default_rng(6)
+    for _ in range(20):
+        P, Lq = int(rng.integers(1, 40)), int(rng.integers(1, 9))
+        lens = [int(x) for x in rng.integers(1, 60, size=int(rng.integers(1, 7)))]
+        st = sp_synth.forkjoin_segtable(P, [lens], Lq)
+        tree = orc.equilibrium_positions_tree(st.seg_parent, st.seg_tok_len)
+        pp, pd, pq = orc.equilibrium_positions(P, lens, Lq)
+        np.testing.assert_allclose(tree[0], pp, atol=1e-12)
+        for i in range(len(lens)):
+            np.testing.assert_allclose(tree[st.doc_seg[i]], pd[i], atol=1e-12)
+            np.testing.assert_allclose(tree[st.query_seg[i]], pq, atol=1e-12)
+    # random forests: siblings start together and cover the same span (the harmonic mean of their
+    # lengths); positions increase strictly along every root-to-leaf chain
+    for _ in range(20):
+        n = int(rng.integers(2, 14))
+        parents = [-1] + [int(rng.integers(-1, s)) for s in range(1, n)]
+        lens = [int(x) for x in rng.integers(1, 9, size=n)]
+        pos = orc.equilibrium_positions_tree(parents, lens)
+        for s in range(n):
+            sib = [c for c in range(n) if parents[c] == parents[s] and parents[s] >= 0]
+            if parents[s] >= 0:
+                S = orc.harmonic_span([lens[c] for c in sib])
+                step = S / lens[s]
+                assert abs((pos[s][-1] + step) - (pos[sib[0]][0] + S)) < 1e-9      # span ends S after the common start
+                assert abs(pos[s][0] - pos[sib[0]][0]) < 1e-12
+                assert pos[s][0] > pos[parents[s]][-1]                              # strictly after the parent
+            assert np.all(np.diff(pos[s]) > 0)
+
