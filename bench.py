@@ -54,6 +54,51 @@ def decode_step_bytes(n_keys_total: int, n_kv_heads: int, head_dim: int, esz: in
     return n_keys_total * kv_bytes_per_token(n_kv_heads, head_dim, esz)
 
 
+N_WARM, N_TRIALS = 10, 30      # side legs: warm-up launches, timed trials (median of 30, as in App. C)
+
+
+def _time_launches(torch, launch, n_warm=N_WARM, n_trials=N_TRIALS):
+    """Times `launch(i)` with events on the launch stream (torch's current stream, which is the stream the
+    binding enqueues on): n_warm untimed calls, then n_trials timed ones.  Returns ms statistics."""
+    for i in range(n_warm):
+        launch(i)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_trials + 1)]
+    ev[0].record()
+    for i in range(n_trials):
+        launch(i)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    t = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(n_trials)])
+    return {"median_ms": round(float(np.median(t)), 4), "min_ms": round(float(t.min()), 4),
+            "p90_ms": round(float(np.percentile(t, 90)), 4), "mean_ms": round(float(t.mean()), 4),
+            "warmup": n_warm, "trials": n_trials}
+
+
+def _stored_traffic(key):
+    """HBM bytes per launch from the committed counter runs (profiles/traffic.json): a STORED figure, not
+    measured in this run."""
+    try:
+        v = json.load(open(os.path.join(ROOT, "profiles", "traffic.json"))).get(key)
+    except Exception:
+        v = None
+    return v
+
+
+def _prefill_roofline(ms, flops, bytes_, traffic_key):
+    """Both roofs of one prefill launch: HBM (the binding one at these shapes) and bf16 MFMA, plus the
+    fraction of min(MFMA peak, intensity x HBM peak)."""
+    t = ms * 1e-3
+    tf, gb = flops / t / 1e12, bytes_ / t / 1e9
+    ceil_tf = min(MFMA_BF16_PEAK_TFLOPS, flops / bytes_ * HBM_PEAK_GBS / 1e3)
+    return {"tflops": round(tf, 2), "mfma_frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "hbm_GBps": round(gb, 1),
+            "hbm_frac": round(gb / HBM_PEAK_GBS, 4), "algorithmic_flops": int(flops), "algorithmic_bytes": int(bytes_),
+            "intensity_flop_per_byte": round(flops / bytes_, 1),
+            "hbm_ceiling_frac_of_mfma_peak": round(ceil_tf / MFMA_BF16_PEAK_TFLOPS, 4),
+            "frac_of_binding_ceiling": round(tf / ceil_tf, 4),
+            "traffic": _stored_traffic(traffic_key), "traffic_source": "stored: profiles/traffic.json (rocprofv3 --pmc runs)"}
+
+
 def _device_inputs(wl, seed, torch):
     """One input set of the workload, generated on the device from a seeded generator."""
     g = torch.Generator(device="cuda")
@@ -141,13 +186,15 @@ def main():
     ap.add_argument("--no-graph", action="store_true",
                     help="skip the leg that replays the whole step from a captured HIP graph")
     ap.add_argument("--no-other-workloads", action="store_true",
-                    help="skip the prefill-only legs on the ragged and the grouped-query workloads")
+                    help="skip the prefill and saliency legs on the ragged and the grouped-query workloads")
     ap.add_argument("--no-online-prefill", action="store_true",
-                    help="skip the path-cached (query rows only) prefill leg, e.g. so that a kernel trace of this "
-                         "run holds full prefill launches only")
+                    help="skip the path-cached (query rows only) and iterative-round prefill legs, e.g. so that a "
+                         "kernel trace of this run holds full prefill launches only")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="short run for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE: a plain elementwise kernel of known "
-                         "traffic (calibration), then a few steps; prints no benchmark line")
+                         "traffic (calibration), then a few launches of every leg; prints no benchmark line")
+    ap.add_argument("--only", default=None, choices=["decode_c5", "c3_ragged_bf16", "c4_gqa_bf16"],
+                    help="run one side leg alone (for a kernel trace that holds nothing else); prints its block")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (one process, one MI355X); --gpus %d is not "
@@ -157,19 +204,19 @@ def main():
     import torch
     from paper_2404_06910_amd import binding as B
 
-    wl = sp_synth.WORKLOADS[args.workload]
-    assert wl.dtype == "bf16"
     torch.cuda.set_device(0)
     ctx = B.Context(0)                       # launches on torch's current stream
+    if args.only:
+        if args.only == "decode_c5":
+            print(json.dumps({"decode_c5": _bench_decode_c5(ctx, torch, B)}))
+        else:
+            print(json.dumps({args.only: _bench_workload_leg(ctx, torch, B, args.only, bias=False)}))
+        return
+    wl = sp_synth.WORKLOADS[args.workload]
+    assert wl.dtype == "bf16"
     sets = [_device_inputs(wl, wl.seed + 17 * i, torch) for i in range(2)]
     st = sets[0]["st"]
-    plans = []
-    t_plan = time.perf_counter()
-    for s in sets:
-        t = s["st"]
-        plans.append(B.Plan(ctx, t.prompt_seg_off, t.seg_tok_start, t.seg_tok_len, t.seg_parent, t.seg_path,
-                            t.n_tokens, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, B.SP_BF16))
-    t_plan = (time.perf_counter() - t_plan) / len(sets)
+    plans = [_make_plan(ctx, B, wl, s["st"]) for s in sets]
     scale = 1 / math.sqrt(wl.head_dim)
     S = wl.decode_steps
     path_off_dev = [p.path_offsets_device() for p in plans]
@@ -194,8 +241,15 @@ def main():
         y = torch.empty_like(x)
         for _ in range(3):
             torch.add(x, 1, out=y)
+        del x, y
         for i in range(max(args.steps, 2)):
             step(i)
+        _bench_online_prefill(ctx, torch, B, wl, sets, scale, n_warm=1, n_trials=3)
+        _bench_iterative_round(ctx, torch, B, wl, sets, scale, n_warm=1, n_trials=3)
+        torch.cuda.synchronize()
+        del sets
+        for name in ("c3_ragged_bf16", "c4_gqa_bf16"):
+            _bench_workload_leg(ctx, torch, B, name, bias=False, n_warm=1, n_trials=3)
         _bench_decode_c5(ctx, torch, B, steps=8, reps=1)
         torch.cuda.synchronize()
         print(json.dumps({"traffic_probe": True, "calibration_kernel": "torch.add bf16, 2^30 B read + 2^30 B written"}))
@@ -210,8 +264,9 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ph = np.array([[ev[j].elapsed_time(ev[j + 1]) for j in range(4)] for ev in events])   # ms
-    med = np.median(ph, axis=0)
-    mean = ph.mean(axis=0)
+    med, mean, mn, p90 = np.median(ph, axis=0), ph.mean(axis=0), ph.min(axis=0), np.percentile(ph, 90, axis=0)
+    names = ["prefill", "saliency", "topk", "decode_%d_steps" % S]
+    stat = lambda v: {n: round(float(x), 4) for n, x in zip(names, v)}
 
     pairs = plans[0].visible_pairs()
     flops = prefill_flops(pairs, wl.n_q_heads, wl.head_dim)
@@ -232,39 +287,34 @@ def main():
                    "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "preamble": wl.preamble_len,
                    "doc_len": wl.doc_len, "query_len": wl.query_len, "vocab": wl.vocab, "top_k": wl.top_k,
                    "decode_steps": S, "tokens": st.n_tokens, "input_sets_rotated": 2},
-        "phase_ms_mean": {"prefill": round(mean[0], 4), "saliency": round(mean[1], 4), "topk": round(mean[2], 4),
-                          "decode_%d_steps" % S: round(mean[3], 4)},
-        "phase_ms_median": {"prefill": round(med[0], 4), "saliency": round(med[1], 4), "topk": round(med[2], 4),
-                            "decode_%d_steps" % S: round(med[3], 4)},
-        "plan_create_ms": round(t_plan * 1e3, 3),
+        "phase_ms_mean": stat(mean), "phase_ms_median": stat(med), "phase_ms_min": stat(mn), "phase_ms_p90": stat(p90),
+        "plan_create_ms": _plan_create_ms(ctx, B, wl, st),
         # dominant kernel: prefill.  Its arithmetic intensity at this shape (flops/compulsory bytes) is
         # below the machine balance, so HBM is the binding roof; the MFMA view is given next to it.
         "roofline": {"kernel": "prefill_bf16_kernel", "bound": "hbm", "achieved": round(pbytes / t_pre / 1e9, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(pbytes / t_pre / 1e9 / HBM_PEAK_GBS, 4),
-                     "traffic": None, "algorithmic_bytes": pbytes, "algorithmic_flops": flops,
-                     "intensity_flop_per_byte": round(flops / pbytes, 1), "avg_launch_ms": round(mean[0], 4)},
+                     "traffic": _stored_traffic("prefill_bf16_kernel:" + wl.name),
+                     "traffic_source": "stored: profiles/traffic.json (rocprofv3 --pmc runs, not counted in this run)",
+                     "algorithmic_bytes": pbytes, "algorithmic_flops": flops,
+                     "intensity_flop_per_byte": round(flops / pbytes, 1), "avg_launch_ms": round(mean[0], 4),
+                     "median_launch_ms": round(med[0], 4), "min_launch_ms": round(mn[0], 4)},
         "roofline_mfma": {"kernel": "prefill_bf16_kernel", "bound": "mfma", "achieved": round(tflops, 2),
                           "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                           "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
                           "hbm_ceiling_frac": round(flops / pbytes * HBM_PEAK_GBS * 1e9 / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)},
-        "saliency": {"kernel": "row_loglik_kernel", "bound": "hbm", "achieved": round(sal_gbs, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(sal_gbs / HBM_PEAK_GBS, 4), "algorithmic_bytes": sal_bytes},
+        "saliency": {"kernel": "saliency_kernel", "bound": "hbm", "achieved": round(sal_gbs, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(sal_gbs / HBM_PEAK_GBS, 4), "algorithmic_bytes": sal_bytes,
+                     "median_ms": round(med[1], 4), "min_ms": round(mn[1], 4), "p90_ms": round(p90[1], 4),
+                     "traffic": _stored_traffic("saliency_kernel:" + wl.name),
+                     "traffic_source": "stored: profiles/traffic.json"},
         "decode_in_step": {"kernel": "decode_kernel", "bound": "hbm", "achieved": round(dec_gbs, 1),
                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dec_gbs / HBM_PEAK_GBS, 4),
                            "algorithmic_bytes": dec_bytes, "note": "8 prompts only: launch-latency bound"},
     }
-    tr = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tr):
-        try:
-            tj = json.load(open(tr))
-            out["roofline"]["traffic"] = tj.get("prefill_bf16_kernel:" + wl.name)
-            out["saliency"]["traffic"] = tj.get("row_loglik_kernel:" + wl.name)
-        except Exception:
-            pass
 
     if not args.no_graph:
         # the same step, captured once per input set into a HIP graph and replayed (launch overhead of
-        # the nine kernels of a step leaves the host)
+        # the eight kernels of a step leaves the host)
         graphs = []
         for j in range(2):
             g = torch.cuda.CUDAGraph()
@@ -282,15 +332,18 @@ def main():
         torch.cuda.synchronize()
         out["graph_replay"] = {"ms_per_step": round((time.perf_counter() - t0) / args.steps * 1e3, 4),
                                "eager_ms_per_step": out["ms_per_step"]}
+        del graphs
     if not args.no_online_prefill:
         out["prefill_online_cached"] = _bench_online_prefill(ctx, torch, B, wl, sets, scale)
-    if not args.no_online_prefill:
         out["prefill_iterative_round"] = _bench_iterative_round(ctx, torch, B, wl, sets, scale)
+    del sets, plans
+    torch.cuda.empty_cache()
     if not args.no_other_workloads:
-        out["prefill_other_workloads"] = {
-            "c3_ragged_bf16": _bench_prefill_leg(ctx, torch, B, "c3_ragged_bf16", bias=False),
-            "c3_ragged_bf16+equilibrium_bias": _bench_prefill_leg(ctx, torch, B, "c3_ragged_bf16", bias=True),
-            "c4_gqa_bf16": _bench_prefill_leg(ctx, torch, B, "c4_gqa_bf16", bias=False),
+        out["other_workloads"] = {
+            "c3_ragged_bf16": _bench_workload_leg(ctx, torch, B, "c3_ragged_bf16", bias=False),
+            "c3_ragged_bf16+equilibrium_bias": _bench_workload_leg(ctx, torch, B, "c3_ragged_bf16", bias=True,
+                                                                   saliency=False),
+            "c4_gqa_bf16": _bench_workload_leg(ctx, torch, B, "c4_gqa_bf16", bias=False),
         }
     if not args.no_decode_c5:
         out["decode_c5"] = _bench_decode_c5(ctx, torch, B)
@@ -301,11 +354,31 @@ def main():
     print(json.dumps(out))
 
 
-def _bench_prefill_leg(ctx, torch, B, name, bias, reps=12):
-    """Prefill only, on another workload; with bias = True the tokens carry equilibrium positions
-    (Sec. 3.2.2 Eq. 1, from the library's host helper) and every head a linear distance penalty."""
+def _make_plan(ctx, B, wl, st, **kw):
+    return B.Plan(ctx, st.prompt_seg_off, st.seg_tok_start, st.seg_tok_len, st.seg_parent, st.seg_path, st.n_tokens,
+                  wl.n_q_heads, wl.n_kv_heads, wl.head_dim, B.SP_BF16, **kw)
+
+
+def _plan_create_ms(ctx, B, wl, st, reps=7, **kw):
+    """Host time of one sp_plan_create through the binding (validation, work list, one asynchronous
+    upload), the per-request cost of a new prompt DAG: median of `reps` create/destroy cycles after two
+    warm-up cycles (the device block and the pinned staging buffer are then recycled)."""
+    ts = []
+    for i in range(reps + 2):
+        t0 = time.perf_counter()
+        p = _make_plan(ctx, B, wl, st, **kw)
+        ts.append(time.perf_counter() - t0)
+        p.close()
+    return round(float(np.median(ts[2:])) * 1e3, 3)
+
+
+def _bench_workload_leg(ctx, torch, B, name, bias, saliency=True, n_warm=N_WARM, n_trials=N_TRIALS):
+    """Prefill (and saliency) alone on another workload, two input sets rotated; with bias = True the tokens
+    carry equilibrium positions (Sec. 3.2.2 Eq. 1, from the library's host helper) and every head a linear
+    distance penalty."""
     wl = sp_synth.WORKLOADS[name]
-    sets, plans = [], []
+    sets, plans, sts = [], [], []
+    pos = slopes = None
     for i in range(2):
         seed = wl.seed + 17 * i
         g = torch.Generator(device="cuda"); g.manual_seed(seed)
@@ -314,122 +387,153 @@ def _bench_prefill_leg(ctx, torch, B, name, bias, reps=12):
         rn = lambda h: torch.randn((st.n_tokens, h, wl.head_dim), generator=g, device="cuda").to(torch.bfloat16)
         Q, K, V = rn(wl.n_q_heads), rn(wl.n_kv_heads), rn(wl.n_kv_heads)
         sets.append((Q, K, V, torch.empty_like(Q)))
-        pos = slopes = None
         if bias:
             pos = B.equilibrium_positions(st.prompt_seg_off, st.seg_tok_start, st.seg_tok_len, st.seg_parent,
                                           st.seg_path, st.n_tokens)
             slopes = sp_synth.geometric_slopes(wl.n_q_heads)
-        plans.append(B.Plan(ctx, st.prompt_seg_off, st.seg_tok_start, st.seg_tok_len, st.seg_parent, st.seg_path,
-                            st.n_tokens, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, B.SP_BF16, tok_pos=pos,
-                            alibi_slopes=slopes))
+        plans.append(_make_plan(ctx, B, wl, st, tok_pos=pos, alibi_slopes=slopes))
+        sts.append(st)
     scale = 1 / math.sqrt(wl.head_dim)
-    for i in range(4):
-        ctx.sp_forkjoin_prefill(plans[i % 2], *sets[i % 2], scale)
-    torch.cuda.synchronize()
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
-    ev[0].record()
-    for i in range(reps):
-        ctx.sp_forkjoin_prefill(plans[i % 2], *sets[i % 2], scale)
-        ev[i + 1].record()
-    torch.cuda.synchronize()
-    ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(reps)]))
+    t = _time_launches(torch, lambda i: ctx.sp_forkjoin_prefill(plans[i % 2], *sets[i % 2], scale), n_warm, n_trials)
     flops = float(np.mean([prefill_flops(p.visible_pairs(), wl.n_q_heads, wl.head_dim) for p in plans]))
     by = float(np.mean([prefill_bytes(s[0].shape[0], wl.n_q_heads, wl.n_kv_heads, wl.head_dim, 2) for s in sets]))
-    return {"avg_launch_ms": round(ms, 4), "tflops": round(flops / (ms * 1e-3) / 1e12, 2),
-            "hbm_GBps": round(by / (ms * 1e-3) / 1e9, 1), "hbm_frac": round(by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-            "mfma_frac": round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-            "tokens": int(sets[0][0].shape[0]), "n_prompts": wl.n_prompts}
+    out = {"prefill": dict(t, kernel="prefill_bf16_kernel", bound="hbm",
+                           **_prefill_roofline(t["median_ms"], flops, by, "prefill_bf16_kernel:" + name + ("+bias" if bias else ""))),
+           "tokens": int(sets[0][0].shape[0]), "n_prompts": wl.n_prompts,
+           "plan_create_ms": _plan_create_ms(ctx, B, wl, sts[0], tok_pos=pos, alibi_slopes=slopes)}
+    del sets, plans
+    torch.cuda.empty_cache()
+    if saliency:
+        out["saliency"] = _bench_saliency(ctx, torch, B, wl, n_warm, n_trials)
+    return out
 
 
-def _bench_online_prefill(ctx, torch, B, wl, sets, scale, reps=20):
+def _bench_saliency(ctx, torch, B, wl, n_warm=N_WARM, n_trials=N_TRIALS):
+    """sp_path_saliency alone at the workload's size (rows = prompts x paths x query tokens, its vocabulary),
+    two logit matrices rotated (each far larger than the last-level cache when summed)."""
+    n_slots = wl.n_prompts * wl.n_paths
+    R = n_slots * wl.query_len
+    g = torch.Generator(device="cuda"); g.manual_seed(wl.seed + 5)
+    mats = []
+    for _ in range(2):
+        x = torch.empty((R, wl.vocab), dtype=torch.bfloat16, device="cuda")
+        for r in range(0, R, 512):
+            n = min(512, R - r)
+            x[r:r + n] = torch.randn((n, wl.vocab), generator=g, device="cuda") * wl.logit_std
+        mats.append(x)
+    rng = np.random.default_rng(wl.seed + 6)
+    tgt = torch.from_numpy(rng.integers(0, wl.vocab, size=R).astype(np.int32)).cuda()
+    rp = torch.from_numpy(np.repeat(np.arange(n_slots), wl.query_len).astype(np.int32)).cuda()
+    score = torch.empty(n_slots, device="cuda")
+    t = _time_launches(torch, lambda i: ctx.sp_path_saliency(mats[i % 2], tgt, rp, n_slots, score), n_warm, n_trials)
+    by = R * wl.vocab * 2
+    gbs = by / (t["median_ms"] * 1e-3) / 1e9
+    out = dict(t, kernel="saliency_kernel", bound="hbm", achieved=round(gbs, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+               frac=round(gbs / HBM_PEAK_GBS, 4), algorithmic_bytes=by, rows=R, vocab=wl.vocab,
+               traffic=_stored_traffic("saliency_kernel:" + wl.name), traffic_source="stored: profiles/traffic.json")
+    del mats
+    torch.cuda.empty_cache()
+    return out
+
+
+def _bench_online_prefill(ctx, torch, B, wl, sets, scale, n_warm=N_WARM, n_trials=N_TRIALS):
     """Path-cached split (Sec. 3.3.1, Alg. 2): preamble and document K/V are resident from an offline
     pass; the online launch computes the query-copy rows only (keys: the whole path)."""
-    plans = []
+    plans, cacheds = [], []
     for s in sets:
         t = s["st"]
         cached = np.ones(t.n_segments, np.uint8); cached[np.asarray(t.query_seg)] = 0
-        plans.append(B.Plan(ctx, t.prompt_seg_off, t.seg_tok_start, t.seg_tok_len, t.seg_parent, t.seg_path,
-                            t.n_tokens, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, B.SP_BF16, seg_cached=cached))
-    for i in range(4):
+        plans.append(_make_plan(ctx, B, wl, t, seg_cached=cached))
+        cacheds.append(cached)
+
+    def launch(i):
         d = sets[i % 2]
         ctx.sp_forkjoin_prefill(plans[i % 2], d["Q"], d["K"], d["V"], d["O"], scale)
-    torch.cuda.synchronize()
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
-    ev[0].record()
-    for i in range(reps):
-        d = sets[i % 2]
-        ctx.sp_forkjoin_prefill(plans[i % 2], d["Q"], d["K"], d["V"], d["O"], scale)
-        ev[i + 1].record()
-    torch.cuda.synchronize()
-    ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(reps)]))
+
+    tm = _time_launches(torch, launch, n_warm, n_trials)
+    ms = tm["median_ms"]
     t = sets[0]["st"]
     q_rows = int(sum(int(t.seg_tok_len[s]) for s in np.asarray(t.query_seg)))
     kvb = t.n_tokens * kv_bytes_per_token(wl.n_kv_heads, wl.head_dim, 2)
     qob = q_rows * 2 * wl.n_q_heads * wl.head_dim * 2
     flops = prefill_flops(plans[0].visible_pairs(), wl.n_q_heads, wl.head_dim)
     gbs = (kvb + qob) / (ms * 1e-3) / 1e9
-    return {"kernel": "prefill_bf16_kernel", "rows": "query copies only", "avg_launch_ms": round(ms, 4),
-            "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(gbs / HBM_PEAK_GBS, 4), "algorithmic_bytes": kvb + qob, "algorithmic_flops": flops,
-            "tflops": round(flops / (ms * 1e-3) / 1e12, 2)}
+    return dict(tm, kernel="prefill_bf16_kernel", rows="query copies only", bound="hbm", achieved=round(gbs, 1),
+                peak=HBM_PEAK_GBS, unit="GB/s", frac=round(gbs / HBM_PEAK_GBS, 4), algorithmic_bytes=kvb + qob,
+                algorithmic_flops=flops, tflops=round(flops / (ms * 1e-3) / 1e12, 2),
+                traffic=_stored_traffic("prefill_bf16_kernel:" + wl.name + ":online_cached"),
+                traffic_source="stored: profiles/traffic.json",
+                plan_create_ms=_plan_create_ms(ctx, B, wl, t, seg_cached=cacheds[0]))
 
 
-def _bench_iterative_round(ctx, torch, B, wl, sets, scale, chain=(3, 7, 11, 15), reps=12):
+def _iterative_round_table(t, chain):
+    """Segment table of a later round of iterative superposition on the token pool of table t: the documents
+    kept so far (`chain`) form a cached chain behind the preamble, the others fork behind its tail."""
+    start, length, parent, path, cached, off = [], [], [], [], [], [0]
+    for b in range(t.n_prompts):
+        p0, p1 = int(t.path_off[b]), int(t.path_off[b + 1])
+        base = len(start)
+        ps = int(t.preamble_seg[b])
+        start.append(int(t.seg_tok_start[ps])); length.append(int(t.seg_tok_len[ps])); parent.append(-1)
+        path.append(-1); cached.append(1)
+        tail = base
+        for c in chain:
+            ds = int(t.doc_seg[p0 + c])
+            start.append(int(t.seg_tok_start[ds])); length.append(int(t.seg_tok_len[ds])); parent.append(tail)
+            path.append(-1); cached.append(1)
+            tail = len(start) - 1
+        j = 0
+        for i in range(p1 - p0):
+            if i in chain:
+                continue
+            ds, qs = int(t.doc_seg[p0 + i]), int(t.query_seg[p0 + i])
+            start.append(int(t.seg_tok_start[ds])); length.append(int(t.seg_tok_len[ds])); parent.append(tail)
+            path.append(j); cached.append(0)
+            start.append(int(t.seg_tok_start[qs])); length.append(int(t.seg_tok_len[qs]))
+            parent.append(len(start) - 2); path.append(j); cached.append(0)
+            j += 1
+        off.append(len(start))
+    i32 = lambda a: np.asarray(a, np.int32)
+    return i32(off), i32(start), i32(length), i32(parent), i32(path), np.asarray(cached, np.uint8)
+
+
+def _bench_iterative_round(ctx, torch, B, wl, sets, scale, chain=(3, 7, 11, 15), n_warm=N_WARM, n_trials=N_TRIALS):
     """A later round of iterative superposition (Sec. 4.1.2, App. B) on the same token pool: the
     documents kept so far form a cached chain behind the preamble and the remaining documents, each
     with its query copy, are superposed behind the chain's tail.  Their ancestors are several
     separate token ranges (preamble, the chain's documents)."""
-    plans = []
+    plans, tabs = [], []
     for s in sets:
         t = s["st"]
-        start, length, parent, path, cached, off = [], [], [], [], [], [0]
-        for b in range(t.n_prompts):
-            p0, p1 = int(t.path_off[b]), int(t.path_off[b + 1])
-            base = len(start)
-            ps = int(t.preamble_seg[b])
-            start.append(int(t.seg_tok_start[ps])); length.append(int(t.seg_tok_len[ps])); parent.append(-1)
-            path.append(-1); cached.append(1)
-            tail = base
-            for c in chain:
-                ds = int(t.doc_seg[p0 + c])
-                start.append(int(t.seg_tok_start[ds])); length.append(int(t.seg_tok_len[ds])); parent.append(tail)
-                path.append(-1); cached.append(1)
-                tail = len(start) - 1
-            j = 0
-            for i in range(p1 - p0):
-                if i in chain:
-                    continue
-                ds, qs = int(t.doc_seg[p0 + i]), int(t.query_seg[p0 + i])
-                start.append(int(t.seg_tok_start[ds])); length.append(int(t.seg_tok_len[ds])); parent.append(tail)
-                path.append(j); cached.append(0)
-                start.append(int(t.seg_tok_start[qs])); length.append(int(t.seg_tok_len[qs]))
-                parent.append(len(start) - 2); path.append(j); cached.append(0)
-                j += 1
-            off.append(len(start))
-        i32 = lambda a: np.asarray(a, np.int32)
-        plans.append(B.Plan(ctx, i32(off), i32(start), i32(length), i32(parent), i32(path), t.n_tokens,
-                            wl.n_q_heads, wl.n_kv_heads, wl.head_dim, B.SP_BF16,
-                            seg_cached=np.asarray(cached, np.uint8)))
-    for i in range(4):
+        off, start, length, parent, path, cached = _iterative_round_table(t, chain)
+        plans.append(B.Plan(ctx, off, start, length, parent, path, t.n_tokens, wl.n_q_heads, wl.n_kv_heads,
+                            wl.head_dim, B.SP_BF16, seg_cached=cached))
+        tabs.append((off, start, length, parent, path, cached, t.n_tokens))
+
+    def launch(i):
         d = sets[i % 2]
         ctx.sp_forkjoin_prefill(plans[i % 2], d["Q"], d["K"], d["V"], d["O"], scale)
-    torch.cuda.synchronize()
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
-    ev[0].record()
-    for i in range(reps):
-        d = sets[i % 2]
-        ctx.sp_forkjoin_prefill(plans[i % 2], d["Q"], d["K"], d["V"], d["O"], scale)
-        ev[i + 1].record()
-    torch.cuda.synchronize()
-    ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(reps)]))
+
+    tm = _time_launches(torch, launch, n_warm, n_trials)
+    ms = tm["median_ms"]
     flops = prefill_flops(plans[0].visible_pairs(), wl.n_q_heads, wl.head_dim)
-    return {"kernel": "prefill_bf16_kernel", "rows": "documents not yet kept and their query copies",
-            "chain_documents": len(chain), "avg_launch_ms": round(ms, 4), "algorithmic_flops": flops,
-            "tflops": round(flops / (ms * 1e-3) / 1e12, 2),
-            "mfma_frac": round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+    # per-round cost of the new table: the plan object is rebuilt in place (sp_plan_update)
+    ts = []
+    off, start, length, parent, path, cached, n_tok = tabs[0]
+    for i in range(9):
+        t0 = time.perf_counter()
+        plans[0].update(off, start, length, parent, path, n_tok, seg_cached=cached)
+        ts.append(time.perf_counter() - t0)
+    torch.cuda.synchronize()
+    return dict(tm, kernel="prefill_bf16_kernel", rows="documents not yet kept and their query copies",
+                chain_documents=len(chain), algorithmic_flops=flops, tflops=round(flops / (ms * 1e-3) / 1e12, 2),
+                mfma_frac=round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                traffic=_stored_traffic("prefill_bf16_kernel:" + wl.name + ":iterative_round"),
+                traffic_source="stored: profiles/traffic.json",
+                plan_update_ms=round(float(np.median(ts[2:])) * 1e3, 3))
 
 
-def _bench_decode_c5(ctx, torch, B, steps=None, reps=5, bias=False):
+def _bench_decode_c5(ctx, torch, B, steps=None, reps=7, bias=False):
     """Long pruned decode: 64 prompts, 2 of 20 paths kept, 256 steps over the growing cache.
     With bias = True the cache carries equilibrium positions and every head a distance penalty."""
     wl = sp_synth.WORKLOADS["c5_decode_bf16"]
@@ -475,7 +579,11 @@ def _bench_decode_c5(ctx, torch, B, steps=None, reps=5, bias=False):
     gbs = total / (ms * 1e-3) / 1e9
     return {"workload": wl.name, "kernel": "decode_kernel", "bound": "hbm", "achieved": round(gbs, 1),
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "algorithmic_bytes": total,
-            "loop_ms_median": round(ms, 3), "us_per_step": round(ms * 1e3 / S, 2), "steps": S}
+            "loop_ms_median": round(ms, 3), "loop_ms_min": round(float(np.min(times)), 3),
+            "loop_ms_p90": round(float(np.percentile(times, 90)), 3), "loops_timed": reps, "warmup_loops": 1,
+            "us_per_step": round(ms * 1e3 / S, 2), "steps": S,
+            "traffic": _stored_traffic("decode_kernel:" + wl.name + ("+bias" if bias else "")),
+            "traffic_source": "stored: profiles/traffic.json (bytes per step, mean over the steps traced)"}
 
 
 if __name__ == "__main__":

@@ -20,9 +20,9 @@
  *   n_kv_heads (query head h reads KV head h / (n_q_heads / n_kv_heads)).
  *   Threads: a context (and the plans made on it) is used by one host thread at a time;
  *   different contexts are independent.  The launching calls only enqueue kernels (no memsets; the
- *   saliency accumulators are allocated in sp_create for 16384 path slots, and a call that needs more
- *   allocates a larger block once and keeps the old one until sp_destroy, so a captured graph never
- *   names freed memory), so they may be captured into a HIP graph on the context's stream.
+ *   saliency workspace is allocated in sp_create for 65536 rows and 16384 path slots, and a call that
+ *   needs more allocates a larger block once and keeps the old one until sp_destroy, so a captured graph
+ *   never names freed memory), so they may be captured into a HIP graph on the context's stream.
  *   A plan keeps its context alive: sp_destroy may be called before sp_plan_destroy.
  */
 #ifndef SP_H_
@@ -178,12 +178,13 @@ sp_status sp_path_saliency(sp_ctx *ctx, const void *logits, sp_dtype dtype, int6
                            const float *prior, int32_t n_path_slots, sp_saliency_mode mode, float *score);
 /*
  * sp_path_saliency for callers that cannot allocate device memory (code under HIP graph capture,
- * tight serving loops, harnesses that forbid hipMalloc): same arguments, same result, but the
- * per-path accumulators live in a static device array of the library (16384 path slots, 256 KiB + 256 B
- * per GPU, held until the process ends) instead of the context's workspace, and the call makes no
- * hipMalloc / hipFree.  n_path_slots above 16384 returns SP_ERR_UNSUPPORTED.  The array is shared by every
- * call on that GPU: calls that overlap in time on one GPU (different streams or contexts) race; calls on
- * one stream are safe.  Each launch leaves the accumulators it used at zero, the state the next one expects.
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments, same result, but the scratch
+ * memory of the kernels (one log-likelihood per row, the per-path accumulators) is a static device array
+ * of the library, 1.25 MiB per GPU, held until the process ends, instead of the context's workspace, and
+ * the call makes no hipMalloc / hipFree.  Limits: n_rows <= 65536 and n_path_slots <= 16384, else
+ * SP_ERR_UNSUPPORTED.  The array is shared by every call on that GPU: calls that overlap in time on one
+ * GPU (different streams or contexts) race; calls on one stream are safe.  Each launch leaves the
+ * accumulators it used at zero, the state the next one expects.
  */
 sp_status sp_path_saliency_static(sp_ctx *ctx, const void *logits, sp_dtype dtype, int64_t n_rows, int64_t vocab,
                                   int64_t row_stride, const int32_t *target, const int32_t *row_path,

@@ -120,9 +120,9 @@ extern "C" const char *sp_version(void) { return "sp-forkjoin 0.1 (gfx950)"; }
 
 extern "C" const char *sp_last_error(const sp_ctx *ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
 
-static void *alloc_sal(int32_t slots) {
+static void *alloc_sal(int32_t slots, int64_t rows) {
   void *p = nullptr;
-  const size_t bytes = 256 + sizeof(sp::SalSlot) * size_t(slots);
+  const size_t bytes = sp::saliency_scratch_bytes(rows, slots);
   if (hipMalloc(&p, bytes) != hipSuccess) return nullptr;
   if (hipMemset(p, 0, bytes) != hipSuccess) { (void)hipFree(p); return nullptr; }
   return p;
@@ -146,7 +146,8 @@ extern "C" sp_status sp_create(sp_ctx **out, int device, void *hip_stream) {
   if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cu > 0) c->n_cu = cu;
   // the saliency accumulators are allocated here, so that the hot call allocates nothing in the usual case
   c->sal_slots = sp::kSalDefaultSlots;
-  c->sal = alloc_sal(c->sal_slots);
+  c->sal_rows = sp::kSalDefaultRows;
+  c->sal = alloc_sal(c->sal_slots, c->sal_rows);
   if (!c->sal || hipEventCreateWithFlags(&c->stage_ev, hipEventDisableTiming) != hipSuccess) {
     if (c->sal) (void)hipFree(c->sal);
     delete c;
@@ -187,23 +188,25 @@ extern "C" sp_status sp_set_stream(sp_ctx *ctx, void *hip_stream) {
   return SP_OK;
 }
 
-// Saliency accumulators for n_slots path slots.  A block that is too small is replaced and kept until
-// sp_destroy (a captured graph may still name it); nothing is ever freed inside a hot call.
-static sp_status ensure_sal(sp_ctx *ctx, int32_t n_slots) {
-  if (ctx->sal_slots >= n_slots) return SP_OK;
-  int32_t want = ctx->sal_slots;
-  while (want < n_slots) want *= 2;
-  void *p = alloc_sal(want);
-  if (!p) return fail(&ctx->err, SP_ERR_WORKSPACE, "could not allocate accumulators for %d path slots", n_slots);
+// Saliency workspace (per-row log-likelihoods, per-slot accumulators).  A block that is too small is
+// replaced and kept until sp_destroy (a captured graph may still name it); nothing is ever freed inside a
+// hot call, and the usual sizes never allocate: the block made in sp_create covers 65536 rows.
+static sp_status ensure_sal(sp_ctx *ctx, int64_t n_rows, int32_t n_slots) {
+  if (ctx->sal_slots >= n_slots && ctx->sal_rows >= n_rows) return SP_OK;
+  int32_t slots = ctx->sal_slots;
+  int64_t rows = ctx->sal_rows;
+  while (slots < n_slots) slots *= 2;
+  while (rows < n_rows) rows *= 2;
+  void *p = alloc_sal(slots, rows);
+  if (!p) return fail(&ctx->err, SP_ERR_WORKSPACE, "could not allocate the saliency workspace (%lld rows, %d slots)",
+                      (long long)rows, slots);
   ctx->retired.push_back(ctx->sal);
   ctx->sal = p;
-  ctx->sal_slots = want;
+  ctx->sal_slots = slots;
+  ctx->sal_rows = rows;
   return SP_OK;
 }
 
-// ---------------------------------------------------------------------------------------
-// Plan
-// ---------------------------------------------------------------------------------------
 namespace {
 
 // Hand the items of an ordered work list to n_slots workers (n_slots a multiple of 8; worker s belongs
@@ -773,10 +776,10 @@ extern "C" sp_status sp_path_saliency(sp_ctx *ctx, const void *logits, sp_dtype 
                                      mode, score);
   if (st != SP_OK) return st;
   SP_HIP(ctx, hipSetDevice(ctx->device));
-  st = ensure_sal(ctx, n_path_slots);
+  st = ensure_sal(ctx, n_rows, n_path_slots);
   if (st != SP_OK) return st;
   hipError_t e = sp::launch_saliency(logits, dtype, n_rows, vocab, row_stride, target, row_path, prior,
-                                     n_path_slots, int(mode), ctx->sal, score, ctx->stream);
+                                     n_path_slots, int(mode), ctx->sal, ctx->sal_slots, score, ctx->stream);
   if (e != hipSuccess) return fail(&ctx->err, SP_ERR_HIP, "saliency launch: %s", hipGetErrorString(e));
   return SP_OK;
 }
@@ -791,15 +794,15 @@ extern "C" sp_status sp_path_saliency_static(sp_ctx *ctx, const void *logits, sp
   sp_status st = check_saliency_args(ctx, logits, dtype, n_rows, vocab, row_stride, target, row_path, n_path_slots,
                                      mode, score);
   if (st != SP_OK) return st;
-  if (n_path_slots > sp::kSalStaticSlots)
-    return fail(&ctx->err, SP_ERR_UNSUPPORTED, "n_path_slots %d exceeds the static scratch (%d slots)", n_path_slots,
-                sp::kSalStaticSlots);
+  if (n_path_slots > sp::kSalStaticSlots || n_rows > sp::kSalStaticRows)
+    return fail(&ctx->err, SP_ERR_UNSUPPORTED, "%lld rows / %d path slots exceed the static scratch (%lld rows, %d slots)",
+                (long long)n_rows, n_path_slots, (long long)sp::kSalStaticRows, sp::kSalStaticSlots);
   SP_HIP(ctx, hipSetDevice(ctx->device));
   void *scratch_dev = nullptr;
   hipError_t e = sp::saliency_static_scratch(ctx->device, &scratch_dev);
   if (e != hipSuccess) return fail(&ctx->err, SP_ERR_HIP, "static scratch address: %s", hipGetErrorString(e));
   e = sp::launch_saliency(logits, dtype, n_rows, vocab, row_stride, target, row_path, prior, n_path_slots, int(mode),
-                          scratch_dev, score, ctx->stream);
+                          scratch_dev, sp::kSalStaticSlots, score, ctx->stream);
   if (e != hipSuccess) return fail(&ctx->err, SP_ERR_HIP, "saliency launch: %s", hipGetErrorString(e));
   return SP_OK;
 }

@@ -20,9 +20,21 @@ struct SalSlot {
   uint32_t count;
   uint32_t flags;           // 1: a row with lp = -inf, 2: +inf, 4: NaN
 };
-constexpr int kSalDefaultSlots = 16384;                             // path slots a new context has accumulators for
-constexpr int kSalStaticSlots = 16384;                              // path slots of the no-allocation entry point
-constexpr size_t kSalStaticBytes = 256 + sizeof(SalSlot) * size_t(kSalStaticSlots);
+// per-row result of the saliency row kernel: the log-likelihood in fixed point, or flag bits when it is
+// not finite; scored = 0 for rows without a target
+struct RowLp {
+  long long q;
+  uint32_t flags;
+  uint32_t scored;
+};
+constexpr int64_t kSalDefaultRows = int64_t(1) << 16;               // what a new context's workspace is sized for
+constexpr int kSalDefaultSlots = 16384;
+constexpr int64_t kSalStaticRows = int64_t(1) << 16;                // limits of the no-allocation entry point
+constexpr int kSalStaticSlots = 16384;
+inline size_t saliency_scratch_bytes(int64_t rows, int32_t slots) {
+  return 256 + sizeof(SalSlot) * size_t(slots) + sizeof(RowLp) * size_t(rows);
+}
+constexpr size_t kSalStaticBytes = 256 + size_t(kSalStaticRows) * sizeof(RowLp) + sizeof(SalSlot) * size_t(kSalStaticSlots);
 
 // A run of segments fused on the query side: child segments that are packed directly behind
 // their parent continue the parent's causal sequence (Sec. 3.2: a chain is a classical prompt).
@@ -92,8 +104,9 @@ struct sp_ctx {
   int n_cu = 256;             // compute units of the device (read once)
   // saliency accumulators (zero between launches); a block that became too small is kept until
   // sp_destroy, because a captured graph may still name it
-  void *sal = nullptr;
+  void *sal = nullptr;        // [launch counter][sal_slots accumulators][sal_rows per-row values]
   int32_t sal_slots = 0;
+  int64_t sal_rows = 0;
   std::vector<void *> retired;
   // plan upload: one pinned staging buffer, one event that tells when its last copy has left it,
   // and the device blocks of destroyed plans, kept for the next plan
@@ -152,7 +165,7 @@ hipError_t launch_prefill_f32(const sp_plan *plan, const PrefillArgs &a, hipStre
 
 hipError_t launch_saliency(const void *logits, sp_dtype dt, int64_t n_rows, int64_t vocab, int64_t row_stride,
                            const int32_t *target, const int32_t *row_path, const float *prior,
-                           int32_t n_slots, int mode, void *scratch_dev, float *score, hipStream_t s);
+                           int32_t n_slots, int mode, void *scratch, int32_t cap_slots, float *score, hipStream_t s);
 hipError_t saliency_static_scratch(int device, void **out);
 
 hipError_t launch_topk(const float *score, const int32_t *path_off, int32_t n_prompts, int32_t n_paths_max,

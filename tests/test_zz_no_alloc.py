@@ -34,14 +34,24 @@ def test_static_scratch_entry_point_matches_the_allocating_one():
         a = torch.full((n,), float("nan"), device="cuda")
         b = torch.full((n,), float("nan"), device="cuda")
         ctx.sp_path_saliency(X, T, P, n, a, prior=PR, mode=mode)
-        before = torch.cuda.memory_allocated()
-        ctx.sp_path_saliency_static(X, T, P, n, b, prior=PR, mode=mode)
-        assert torch.cuda.memory_allocated() == before
         torch.cuda.synchronize()
+        free_before = torch.cuda.mem_get_info()[0]              # device-wide: sees any hipMalloc, not only torch's
+        ctx.sp_path_saliency_static(X, T, P, n, b, prior=PR, mode=mode)
+        torch.cuda.synchronize()
+        assert torch.cuda.mem_get_info()[0] == free_before
         got_a, got_b = a.cpu().numpy(), b.cpu().numpy()
         assert np.array_equal(got_a, got_b), (got_a, got_b)
         ref = orc.path_saliency(x, tgt, rp, n, prior=prior, mode="mean" if mode == B.SALIENCY_MEAN else "sum")
         np.testing.assert_allclose(got_b, ref, rtol=1e-3, atol=1e-5)
+    # many slots and rows scattered over them: per-lane atomics into the static array's accumulators
+    R, n, vocab = 96, 5000, 520
+    x, tgt, rp, prior = _case(rng, R, n, vocab, "f32")
+    X, T, P = dev(x, "f32"), dev(tgt), dev(rp)
+    for _ in range(2):                                          # twice: the accumulators must come back to zero
+        b = torch.full((n,), float("nan"), device="cuda")
+        ctx.sp_path_saliency_static(X, T, P, n, b)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(b.cpu().numpy(), orc.path_saliency(x, tgt, rp, n), rtol=1e-3, atol=1e-5)
     # beyond the static maximum: a clear error, nothing launched
     n_big = 16384 + 1
     with pytest.raises(B.SpError) as e:
