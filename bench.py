@@ -400,7 +400,7 @@ def _bench_workload_leg(ctx, torch, B, name, bias, saliency=True, n_warm=N_WARM,
     out = {"prefill": dict(t, kernel="prefill_bf16_kernel", bound="hbm",
                            **_prefill_roofline(t["median_ms"], flops, by, "prefill_bf16_kernel:" + name + ("+bias" if bias else ""))),
            "tokens": int(sets[0][0].shape[0]), "n_prompts": wl.n_prompts,
-           "plan_create_ms": _plan_create_ms(ctx, B, wl, sts[0], tok_pos=pos, alibi_slopes=slopes)}
+           "plan_create_ms": _plan_create_ms(ctx, B, wl, sts[1], tok_pos=pos, alibi_slopes=slopes)}   # pos belongs to sts[1]
     del sets, plans
     torch.cuda.empty_cache()
     if saliency:
@@ -525,8 +525,14 @@ def _bench_iterative_round(ctx, torch, B, wl, sets, scale, chain=(3, 7, 11, 15),
         plans[0].update(off, start, length, parent, path, n_tok, seg_cached=cached)
         ts.append(time.perf_counter() - t0)
     torch.cuda.synchronize()
+    # compulsory bytes: K and V of every token once (cached chain, preamble and computed rows are all keys),
+    # Q read and O written for the rows that are computed
+    off, start, length, parent, path, cached, n_tok = tabs[0]
+    rows = int(sum(int(l) for l, c in zip(length, cached) if not c))
+    by = n_tok * kv_bytes_per_token(wl.n_kv_heads, wl.head_dim, 2) + rows * 2 * wl.n_q_heads * wl.head_dim * 2
     return dict(tm, kernel="prefill_bf16_kernel", rows="documents not yet kept and their query copies",
                 chain_documents=len(chain), algorithmic_flops=flops, tflops=round(flops / (ms * 1e-3) / 1e12, 2),
+                algorithmic_bytes=by, hbm_frac=round(by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                 mfma_frac=round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                 traffic=_stored_traffic("prefill_bf16_kernel:" + wl.name + ":iterative_round"),
                 traffic_source="stored: profiles/traffic.json",

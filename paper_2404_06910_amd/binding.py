@@ -90,11 +90,18 @@ def _np_ptr(a: Optional[np.ndarray]):
 
 
 def _make_table(prompt_seg_off, seg_tok_start, seg_tok_len, seg_parent, seg_path, n_tokens, tok_pos=None,
-                alibi_slopes=None, seg_cached=None):
+                alibi_slopes=None, seg_cached=None, n_q_heads=None):
     keep = [_i32(prompt_seg_off), _i32(seg_tok_start), _i32(seg_tok_len), _i32(seg_parent), _i32(seg_path)]
     pos = None if tok_pos is None else np.ascontiguousarray(np.asarray(tok_pos, dtype=np.float32))
     slopes = None if alibi_slopes is None else np.ascontiguousarray(np.asarray(alibi_slopes, dtype=np.float32))
     cached = None if seg_cached is None else np.ascontiguousarray(np.asarray(seg_cached, dtype=np.uint8))
+    # the C ABI takes plain pointers and cannot see how long the arrays are: check that here
+    n_seg = len(keep[1])
+    for name, a, n in (("seg_tok_len", keep[2], n_seg), ("seg_parent", keep[3], n_seg), ("seg_path", keep[4], n_seg),
+                       ("tok_pos", pos, int(n_tokens)), ("seg_cached", cached, n_seg),
+                       ("alibi_slopes", slopes, n_q_heads)):
+        if a is not None and n is not None and a.size != n:
+            raise ValueError("%s has %d entries, expected %d" % (name, a.size, n))
     t = _SegTable(len(keep[0]) - 1, len(keep[1]), int(n_tokens), _np_ptr(keep[0]), _np_ptr(keep[1]),
                   _np_ptr(keep[2]), _np_ptr(keep[3]), _np_ptr(keep[4]), _np_ptr(pos), _np_ptr(slopes),
                   _np_ptr(cached))
@@ -212,10 +219,11 @@ class Plan:
                  n_tokens: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dtype: int, tok_pos=None,
                  alibi_slopes=None, seg_cached=None):
         t, keep = _make_table(prompt_seg_off, seg_tok_start, seg_tok_len, seg_parent, seg_path, n_tokens, tok_pos,
-                              alibi_slopes, seg_cached)
+                              alibi_slopes, seg_cached, n_q_heads)
         self._h = C.c_void_p()
         self.ctx = ctx
         self.dtype = dtype
+        self.n_q_heads = n_q_heads
         st = lib().sp_plan_create(ctx._h if ctx else None, C.byref(t), n_q_heads, n_kv_heads, head_dim, dtype,
                                   C.byref(self._h))
         del keep
@@ -227,7 +235,7 @@ class Plan:
                alibi_slopes=None, seg_cached=None):
         """sp_plan_update: rebuild this plan in place for another segment table."""
         t, keep = _make_table(prompt_seg_off, seg_tok_start, seg_tok_len, seg_parent, seg_path, n_tokens, tok_pos,
-                              alibi_slopes, seg_cached)
+                              alibi_slopes, seg_cached, self.n_q_heads)
         st = lib().sp_plan_update(self._h, C.byref(t))
         del keep
         if st != 0:

@@ -394,7 +394,7 @@ sp_status build_plan(sp_ctx *ctx, const sp_segtable *t, int32_t n_q_heads, int32
   };
   // --- prefill work list.  Query heads that share a KV head are stacked in one workgroup (4 waves for
   // 4 heads, else 2 waves), each wave owning 32 token rows of one head.
-  // Persistent workgroups, 8 waves per compute unit.  The work list (ordered prompt, head group, tile) is
+  // Persistent workgroups, 8 waves per compute unit.  The work list (ordered as stated below) is
   // handed out by hand_out() above; cost of an item = LDS stages streamed: one for Q plus the K/V stages,
   // plus the epilogue.  The workgroups that share a compute unit do not run equally fast: the instruction
   // arbiter serves the oldest wave of a SIMD first, so a workgroup dispatched in a later round (slot index
@@ -422,12 +422,24 @@ sp_status build_plan(sp_ctx *ctx, const sp_segtable *t, int32_t n_q_heads, int32
       tile_cost[i] = 2 + (rg.anc_keys + all_tiles[i].row0 + all_tiles[i].n_rows + stage_keys - 1) / stage_keys;
     }
     const size_t n_items = all_tiles.size() * size_t(n_hg);
+    // Order of the work list: prompt, row group, head group, tile of the row group.  The tiles of one
+    // path come together (a later tile re-reads the K/V rows that the earlier ones fetch), and the same path
+    // for the next head follows at once: the K/V rows of a token lie side by side in memory for all heads, so
+    // the workgroups of an XCD, which at any time work on a window of consecutive items, read a few contiguous
+    // regions instead of one head's 256-byte rows strided over a whole prompt (measured against prompt, head
+    // group, tile: 6 % faster on ragged 64-path prompts, 4 % on 20 paths, no change with grouped heads).
+    auto for_each_item = [&](auto &&fn) {
+      for (int32_t b = 0; b < B; ++b)
+        for (int32_t a = prompt_tile_off[b], e = a; a < prompt_tile_off[b + 1]; a = e) {
+          while (e < prompt_tile_off[b + 1] && all_tiles[e].group == all_tiles[a].group) ++e;
+          for (int32_t hg = 0; hg < n_hg; ++hg)
+            for (int32_t tl = a; tl < e; ++tl) fn(tl, hg);
+        }
+    };
     std::vector<int32_t> cost(n_items), owner;
     {
       size_t i = 0;
-      for (int32_t b = 0; b < B; ++b)
-        for (int32_t hg = 0; hg < n_hg; ++hg)
-          for (int32_t tl = prompt_tile_off[b]; tl < prompt_tile_off[b + 1]; ++tl) cost[i++] = tile_cost[tl];
+      for_each_item([&](int32_t tl, int32_t) { cost[i++] = tile_cost[tl]; });
     }
     p->n_wg = (((8 / p->waves_per_wg) * n_cu + 7) / 8) * 8;
     const int32_t rounds = 8 / p->waves_per_wg;
@@ -436,10 +448,9 @@ sp_status build_plan(sp_ctx *ctx, const sp_segtable *t, int32_t n_q_heads, int32
     p->items.resize(n_items);
     std::vector<int32_t> at(p->wg_begin.begin(), p->wg_begin.end() - 1);
     size_t i = 0;
-    for (int32_t b = 0; b < B; ++b)
-      for (int32_t hg = 0; hg < n_hg; ++hg)
-        for (int32_t tl = prompt_tile_off[b]; tl < prompt_tile_off[b + 1]; ++tl)
-          p->items[at[owner[i++]]++] = make_item(all_tiles[tl], hg * p->heads_per_wg, hg * p->heads_per_wg / G);
+    for_each_item([&](int32_t tl, int32_t hg) {
+      p->items[at[owner[i++]]++] = make_item(all_tiles[tl], hg * p->heads_per_wg, hg * p->heads_per_wg / G);
+    });
   }
 
   // --- decode gather tables: shared ranges per prompt, ranges per path slot
