@@ -422,30 +422,37 @@ sp_status build_plan(sp_ctx *ctx, const sp_segtable *t, int32_t n_q_heads, int32
       tile_cost[i] = 2 + (rg.anc_keys + all_tiles[i].row0 + all_tiles[i].n_rows + stage_keys - 1) / stage_keys;
     }
     const size_t n_items = all_tiles.size() * size_t(n_hg);
-    // Order of the work list: prompt, chunk of head groups, row group, head group of the chunk, tile of the
-    // row group.  The tiles of one path come together (a later tile re-reads the K/V rows that the earlier
-    // ones fetch), and the same path for the next head follows at once: the K/V (and Q, O) rows of a token lie
-    // side by side in memory for all heads, so the workgroups of an XCD, which at any time work on a window
-    // of consecutive items, touch a few contiguous regions instead of one head's 256-byte rows strided over a
-    // whole prompt (measured against prompt, head group, tile: 7-14 % faster with ungrouped heads, no change
-    // with grouped ones).  Every item of the window also streams its ancestors' K/V, which the XCD's L2
-    // (4 MB) has to keep for all heads of the chunk next to the paths' own rows: the chunk is as many head
-    // groups as keep that shared part within kSharedKvBudget.  Measured on 32 ungrouped heads of 128 dims
-    // behind a 64-token preamble: chunks of 16 heads (this budget) 167 us and 1.04x the compulsory reads,
-    // all 32 heads 172 us and 1.21x, 8 heads 176 us; behind a 576-token chain of kept documents one head
-    // at a time reads 0.99x, all heads together 3x at the same speed.
+    // Order of the work list: [slice of head groups,] prompt, chunk of head groups, row group, head group of
+    // the chunk, tile of the row group.  The tiles of one path come together (a later tile re-reads the K/V
+    // rows that the earlier ones fetch), and the same path for the next head follows at once: the K/V (and
+    // Q, O) rows of a token lie side by side in memory for all heads, so the workgroups of an XCD, which at
+    // any time work on a window of consecutive items, touch a few contiguous regions instead of one head's
+    // 256-byte rows strided over a whole prompt (measured against prompt, head group, tile: 7-14 % faster
+    // with ungrouped heads, no change with grouped ones).  Every item of the window also streams its
+    // ancestors' K/V, which the XCD's L2 (4 MB) has to keep for all heads of the chunk next to the paths' own
+    // rows: the chunk is as many head groups as keep that shared part within kSharedKvBudget.  Measured
+    // without slices on 32 ungrouped heads of 128 dims behind a 64-token preamble: chunks of 16 heads 167 us
+    // and 1.04x the compulsory reads, all 32 heads 172 us and 1.21x, 8 heads 176 us; behind a 576-token
+    // chain of kept documents one head at a time reads 0.99x, all heads together 3x at the same speed.
     constexpr int64_t kSharedKvBudget = int64_t(1) << 19;
+    // When the head groups divide by the 8 XCDs, the list starts with a loop over 8 slices of them: the
+    // cost-balanced cut into one contiguous range per XCD then falls on the slice boundaries, every XCD works
+    // through all prompts on its own heads, and the 8 XCDs are at about the same tokens at the same time,
+    // which keeps the memory-side accesses together across the whole 8 KB of a token (another 2 % at the
+    // same traffic).
+    const int32_t n_slice = n_hg % 8 == 0 ? 8 : 1, per_slice = n_hg / n_slice;
     auto for_each_item = [&](auto &&fn) {
+      for (int32_t x = 0; x < n_slice; ++x)
       for (int32_t b = 0; b < B; ++b) {
         int32_t anc = 1;
         for (int32_t tl = prompt_tile_off[b]; tl < prompt_tile_off[b + 1]; ++tl)
           anc = std::max(anc, p->groups[all_tiles[tl].group].anc_keys);
         const int64_t per_hg = int64_t(anc) * 2 * head_dim * 2;          // K and V rows of one KV head, bf16
-        const int32_t hc = int32_t(std::max<int64_t>(1, std::min<int64_t>(n_hg, kSharedKvBudget / per_hg)));
-        for (int32_t h0 = 0; h0 < n_hg; h0 += hc)
+        const int32_t hc = int32_t(std::max<int64_t>(1, std::min<int64_t>(per_slice, kSharedKvBudget / per_hg)));
+        for (int32_t h0 = x * per_slice; h0 < (x + 1) * per_slice; h0 += hc)
           for (int32_t a = prompt_tile_off[b], e = a; a < prompt_tile_off[b + 1]; a = e) {
             while (e < prompt_tile_off[b + 1] && all_tiles[e].group == all_tiles[a].group) ++e;
-            for (int32_t hg = h0; hg < std::min(n_hg, h0 + hc); ++hg)
+            for (int32_t hg = h0; hg < std::min((x + 1) * per_slice, h0 + hc); ++hg)
               for (int32_t tl = a; tl < e; ++tl) fn(tl, hg);
           }
       }
