@@ -107,7 +107,11 @@ void sp_plan_destroy(sp_plan *plan);
  * error the plan is unchanged.  Tables travel in one asynchronous copy from a pinned staging buffer
  * on the context's stream (also in sp_plan_create), ordered behind the work already enqueued there;
  * device blocks of destroyed plans are kept by the context and reused, so a steady request loop
- * calls neither hipMalloc nor hipFree.  Not for use while the stream is being captured. */
+ * calls neither hipMalloc nor hipFree.  Not for use while the stream is being captured.
+ * Ordering: a plan's tables are replaced (update) or handed to the next plan (destroy, then create)
+ * in the order of the context's stream, so launches that were enqueued on that stream before still
+ * read the old tables.  Work enqueued with the plan on another stream (sp_set_stream in between)
+ * must have finished before the plan is updated or destroyed. */
 sp_status sp_plan_update(sp_plan *plan, const sp_segtable *table);
 
 /* info[0]=n_prompts [1]=n_segments [2]=n_tokens [3]=n_path_slots [4]=n_row_groups (runs of

@@ -124,7 +124,11 @@ static void *alloc_sal(int32_t slots, int64_t rows) {
   void *p = nullptr;
   const size_t bytes = sp::saliency_scratch_bytes(rows, slots);
   if (hipMalloc(&p, bytes) != hipSuccess) return nullptr;
-  if (hipMemset(p, 0, bytes) != hipSuccess) { (void)hipFree(p); return nullptr; }
+  // zero before any stream may use it: the memset runs on the null stream, the kernels on the caller's
+  if (hipMemset(p, 0, bytes) != hipSuccess || hipStreamSynchronize(nullptr) != hipSuccess) {
+    (void)hipFree(p);
+    return nullptr;
+  }
   return p;
 }
 
@@ -213,8 +217,8 @@ namespace {
 // to XCD s / (n_slots / 8)).  The list is cut into 8 contiguous, cost-balanced ranges, one per XCD, and
 // inside a range the items go, in order, each to the worker with the least work so far (ties: the
 // worker that has waited longest) -- the schedule a shared queue would produce, decided here.  At any
-// moment an XCD therefore works on a window of consecutive items (the blocks of one path, the heads
-// and paths of one (prompt, KV head)), whose K/V rows it then finds in its own L2.  Costs are small
+// moment an XCD therefore works on a window of consecutive items (the order of the list, chosen in
+// build_plan, decides what that window touches in memory).  Costs are small
 // positive integers; the least-loaded worker comes out of a bucket queue keyed by load, O(1) per item.
 // Output: owner[i] = worker of item i, and begin[s] = first position of worker s's slice in the
 // permuted list (items of a worker keep their order).  slow_milli[r]: relative slowness, in thousandths,
