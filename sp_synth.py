@@ -4,8 +4,11 @@ This module only *shapes and draws* inputs: the five workload configurations,
 the ForkJoin segment table (preamble -> {doc_i -> query_i}) as plain integer
 arrays, and random tensors drawn from one numpy Generator in a fixed order.
 It contains none of the method's arithmetic (no attention, no softmax, no
-saliency, no position formula) so that the CPU oracle and the HIP path can both
-be fed from it without sharing any computation.
+saliency, no equilibrium-position formula) so that the CPU oracle and the HIP
+path can both be fed from it without sharing any computation.  The one position
+table it can fill is the trivial one of classical prompting (a token's index
+inside its own path, `classical_positions`), which is an input convention, not
+part of the method; `geometric_slopes` likewise only draws a fixed slope vector.
 
 Workload shapes follow the paper's question-answering setting: 20 documents per
 query (Sec. 4.1.1), documents of 64-256 tokens around the reported means of
