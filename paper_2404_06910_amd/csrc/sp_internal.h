@@ -11,7 +11,7 @@
 
 namespace sp {
 
-constexpr int kMaxRanges = 32;     // ancestor key ranges per row group (after merging neighbours)
+constexpr int kMaxRanges = 1024;   // ancestor key ranges per row group (after merging neighbours); a sanity bound, no array depends on it
 constexpr int kPrefillThreads = 256;
 constexpr int kMaxDevices = 64;
 // per-path accumulator of the saliency launch: fixed-point sum of log-likelihoods, scored rows, flags

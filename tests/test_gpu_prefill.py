@@ -110,7 +110,7 @@ def test_general_tree_with_gaps_and_untouched_rows(ctx):
 
 
 @pytest.mark.parametrize("Hq,Hkv,d,n_chain,bias", [(4, 4, 128, 11, False), (8, 2, 128, 6, True), (2, 2, 64, 12, True),
-                                                   (4, 1, 128, 3, False)])
+                                                   (4, 1, 128, 3, False), (2, 2, 128, 40, False)])
 def test_deep_chains_of_separate_ranges(ctx, Hq, Hkv, d, n_chain, bias):
     """A leaf behind a chain of documents that lie apart in the token pool (the shape of a late round
     of iterative superposition): its ancestors are n_chain + 1 separate token ranges, of lengths that

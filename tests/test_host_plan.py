@@ -183,8 +183,8 @@ def test_error_paths_are_decided_on_the_host():
 
 
 def test_too_many_disjoint_ancestor_ranges_is_unsupported():
-    # a 40-deep chain packed in reverse order: no two ancestors are neighbours in token space
-    n = 40
+    # a 1100-deep chain packed in reverse order: no two ancestors are neighbours in token space
+    n = 1100
     start = np.arange(n)[::-1].astype(np.int32) * 2
     t = dict(prompt_seg_off=np.array([0, n], np.int32), seg_tok_start=start, seg_tok_len=np.ones(n, np.int32),
              seg_parent=np.arange(-1, n - 1).astype(np.int32), seg_path=np.full(n, -1, np.int32), n_tokens=2 * n)
