@@ -56,6 +56,9 @@ SMALL = [
     ("bf16", 6, 2, 128, 20, [[45, 77]], 5, "interleaved", False),                         # GQA 3 (odd group)
     ("bf16", 4, 4, 128, 40, [[100, 64, 77], [33, 128]], 24, "interleaved", True),         # ungrouped heads, bias
     ("bf16", 4, 2, 128, 64, [[128, 31], [200]], 9, "grouped", True),                      # GQA 2, bias
+    ("bf16", 8, 8, 64, 16, [[32, 17]], 8, "interleaved", True),                           # one head group per XCD slice
+    ("bf16", 16, 16, 128, 600, [[40, 33]], 8, "interleaved", False),                      # sliced; long preamble: head chunks of 1
+    ("bf16", 4, 4, 128, 1100, [[20, 31]], 4, "grouped", False),                           # unsliced; head chunks of 1
     ("f32", 4, 2, 128, 33, [[47, 20], [64, 3, 9]], 6, "grouped", True),
     ("f32", 2, 2, 64, 1, [[1]], 1, "interleaved", False),                                 # degenerate: 3 tokens
 ]

@@ -274,6 +274,15 @@ def test_work_list_covers_every_row_and_head_once():
             _check_work_list(t, Hq, Hkv)
         cached = (rng.random(len(t["seg_tok_len"])) < 0.4).astype(np.uint8)
         _check_work_list(t, 4, 1, cached=cached)
+        # head groups that divide by the 8 XCDs (the list is sliced by head groups) and that do not
+        for Hq, Hkv in ((8, 8), (16, 16), (32, 8), (12, 12), (24, 3)):
+            _check_work_list(t, Hq, Hkv)
+    # long shared ancestors: the list goes in chunks of head groups (one at a time here), sliced and unsliced
+    for P, Hq, Hkv in ((600, 16, 16), (1100, 4, 4), (1100, 32, 8)):
+        st = sp_synth.forkjoin_segtable(P, [[40, 33], [17]], 8)
+        t = dict(prompt_seg_off=st.prompt_seg_off, seg_tok_start=st.seg_tok_start, seg_tok_len=st.seg_tok_len,
+                 seg_parent=st.seg_parent, seg_path=st.seg_path, n_tokens=st.n_tokens)
+        _check_work_list(t, Hq, Hkv)
     for name in ("c2_mha7b_bf16", "c4_gqa_bf16"):
         wl = sp_synth.WORKLOADS[name]
         st = sp_synth.forkjoin_segtable(wl.preamble_len, [[wl.doc_len] * wl.n_paths] * 2, wl.query_len)
