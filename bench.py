@@ -99,6 +99,22 @@ def _prefill_roofline(ms, flops, bytes_, traffic_key):
             "traffic": _stored_traffic(traffic_key), "traffic_source": "stored: profiles/traffic.json (rocprofv3 --pmc runs)"}
 
 
+def _memory_rate_reference(torch, n_bytes=1 << 29):
+    """What the memory side of this GPU sustains for plain streaming, measured with library element-wise
+    kernels over buffers far larger than the last-level cache: a copy (one read per write) and an
+    addcmul (three reads per write, the mix of the prefill: Q, K, V in, O out).  Context for the roofline
+    fractions, which are quoted against the 8 TB/s peak; not a target."""
+    n = n_bytes // 2
+    a, b, c = (torch.ones(n, dtype=torch.bfloat16, device="cuda") for _ in range(3))
+    d = torch.empty_like(a)
+    t_copy = _time_launches(torch, lambda i: d.copy_(a))
+    t_mix = _time_launches(torch, lambda i: torch.addcmul(a, b, c, out=d))
+    return {"copy_GBps": round(2 * n_bytes / (t_copy["median_ms"] * 1e-3) / 1e9, 1),
+            "three_reads_one_write_GBps": round(4 * n_bytes / (t_mix["median_ms"] * 1e-3) / 1e9, 1),
+            "kernels": "torch copy_ and addcmul on bf16", "bytes_per_buffer": n_bytes,
+            "warmup": N_WARM, "trials": N_TRIALS}
+
+
 def _device_inputs(wl, seed, torch):
     """One input set of the workload, generated on the device from a seeded generator."""
     g = torch.Generator(device="cuda")
@@ -190,6 +206,8 @@ def main():
     ap.add_argument("--no-online-prefill", action="store_true",
                     help="skip the path-cached (query rows only) and iterative-round prefill legs, e.g. so that a "
                          "kernel trace of this run holds full prefill launches only")
+    ap.add_argument("--no-memory-reference", action="store_true",
+                    help="skip the library element-wise kernels that show what this GPU's memory side sustains")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="short run for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE: a plain elementwise kernel of known "
                          "traffic (calibration), then a few launches of every leg; prints no benchmark line")
@@ -349,6 +367,10 @@ def main():
         out["decode_c5"] = _bench_decode_c5(ctx, torch, B)
         if not args.no_other_workloads:
             out["decode_c5+equilibrium_bias"] = _bench_decode_c5(ctx, torch, B, steps=64, reps=3, bias=True)
+    if not args.no_memory_reference:
+        out["memory_rate_reference"] = _memory_rate_reference(torch)
+        ref = out["memory_rate_reference"]["three_reads_one_write_GBps"]
+        out["roofline"]["frac_of_measured_reference"] = round(out["roofline"]["achieved"] / ref, 4)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline(wl)
     print(json.dumps(out))
